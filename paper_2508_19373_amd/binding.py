@@ -1,0 +1,126 @@
+"""ctypes binding of libmoe_shard.so: same names as the C ABI (include/moe_shard.h), argument
+marshalling only.  Tensors are torch CUDA tensors (PyTorch supplies device memory and the
+stream); every step of the path runs in the library's HIP kernels.  There is no fallback: a
+missing library raises at first use."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmoe_shard.so")
+_lib = None
+
+MOE_OK = 0
+MOE_ERR_INVALID_ARG = -1
+MOE_ERR_UNSUPPORTED_SHAPE = -2
+MOE_ERR_WORKSPACE = -3
+MOE_ERR_HIP = -4
+MOE_RENORM_TOPK = 1 << 0
+MOE_LOGITS_GIVEN = 1 << 1
+MOE_Y_PERM_BF16 = 1 << 2
+MOE_OUT_F32 = 1 << 3
+MOE_MAX_EXPERTS = 256
+MOE_MAX_TOPK = 16
+
+EXPORTS = ("moe_route_topk", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_workspace_bytes",
+           "moe_status_string")
+
+
+class MoeShard(ctypes.Structure):
+    _fields_ = [("n_experts", ctypes.c_int32), ("n_local_experts", ctypes.c_int32),
+                ("expert_offset", ctypes.c_int32), ("hidden", ctypes.c_int32),
+                ("inter_full", ctypes.c_int32), ("inter_slice", ctypes.c_int32)]
+
+
+class MoeError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (fn, status_string(status), status))
+
+
+def lib() -> ctypes.CDLL:
+    """Load the HIP library (built in-tree by __graft_entry__.build()).  No CPU fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError("libmoe_shard.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i32, u32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_uint32, ctypes.c_size_t
+        shp = ctypes.POINTER(MoeShard)
+        L.moe_route_topk.argtypes = [vp, vp, vp, i32, i32, i32, i32, u32, vp, vp, vp]
+        L.moe_route_topk.restype = ctypes.c_int
+        L.moe_permute.argtypes = [vp, vp, i32, i32, shp, vp, vp, vp, vp, vp, sz, vp]
+        L.moe_permute.restype = ctypes.c_int
+        L.moe_expert_ffn.argtypes = [vp, vp, i32, shp, vp, vp, vp, vp, vp, u32, vp]
+        L.moe_expert_ffn.restype = ctypes.c_int
+        L.moe_combine.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, u32, vp]
+        L.moe_combine.restype = ctypes.c_int
+        L.moe_workspace_bytes.argtypes = [i32, i32, shp]
+        L.moe_workspace_bytes.restype = sz
+        L.moe_status_string.argtypes = [ctypes.c_int]
+        L.moe_status_string.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().moe_status_string(int(status)).decode()
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_cuda:
+        raise ValueError("device tensor required")
+    if not t.is_contiguous():
+        raise ValueError("contiguous tensor required")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return stream if isinstance(stream, int) else stream.cuda_stream
+
+
+def _check(fn: str, status: int):
+    if status != MOE_OK:
+        raise MoeError(fn, status)
+
+
+def make_shard(n_experts, n_local_experts, expert_offset, hidden, inter_full, inter_slice) -> MoeShard:
+    return MoeShard(n_experts, n_local_experts, expert_offset, hidden, inter_full, inter_slice)
+
+
+def moe_route_topk(x, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream=None):
+    _check("moe_route_topk", lib().moe_route_topk(_ptr(x), _ptr(w_router), _ptr(logits), T, H, E, k, flags,
+                                                  _ptr(topk_idx), _ptr(topk_w), _stream(stream)))
+
+
+def moe_workspace_bytes(T, k, shard: MoeShard) -> int:
+    return int(lib().moe_workspace_bytes(T, k, ctypes.byref(shard)))
+
+
+def moe_permute(x, topk_idx, T, k, shard: MoeShard, x_perm, expert_offsets, row_src, slot_row, workspace,
+                workspace_bytes=None, stream=None):
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    _check("moe_permute", lib().moe_permute(_ptr(x), _ptr(topk_idx), T, k, ctypes.byref(shard), _ptr(x_perm),
+                                            _ptr(expert_offsets), _ptr(row_src), _ptr(slot_row), _ptr(workspace),
+                                            workspace_bytes, _stream(stream)))
+
+
+def moe_expert_ffn(x_perm, expert_offsets, cap_rows, shard: MoeShard, w_gate, w_up, w_down, h_workspace, y_perm,
+                   flags=0, stream=None):
+    _check("moe_expert_ffn", lib().moe_expert_ffn(_ptr(x_perm), _ptr(expert_offsets), cap_rows, ctypes.byref(shard),
+                                                  _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(h_workspace),
+                                                  _ptr(y_perm), flags, _stream(stream)))
+
+
+def moe_combine(y_perm, slot_row, topk_w, T, k, H, y_shared, x, w_shared_gate, y_out, flags=0, stream=None):
+    _check("moe_combine", lib().moe_combine(_ptr(y_perm), _ptr(slot_row), _ptr(topk_w), T, k, H, _ptr(y_shared),
+                                            _ptr(x), _ptr(w_shared_gate), _ptr(y_out), flags, _stream(stream)))

@@ -1,0 +1,51 @@
+// Internal declarations shared by the HIP translation units of libmoe_shard (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moe_shard.h"
+
+namespace moe {
+
+constexpr int kWave = 64;
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+// bf16 bit pattern <-> fp32
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xFFFF0000u); }
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs; NaN stays NaN)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+// launchers (each returns hipGetLastError() after enqueueing on `stream`)
+hipError_t launch_route_topk(const void* x, const float* w_router, float* logits, int T, int H, int E, int k,
+                             uint32_t flags, int32_t* topk_idx, float* topk_w, hipStream_t stream);
+hipError_t launch_permute(const void* x, const int32_t* topk_idx, int T, int k, int H, int n_local, int offset,
+                          void* x_perm, int32_t* expert_offsets, int32_t* row_src, int32_t* slot_row,
+                          hipStream_t stream);
+hipError_t launch_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int cap_rows, int n_local, int H,
+                             int I_s, const void* w_gate, const void* w_up, const void* w_down, void* h_ws,
+                             void* y_perm, bool y_bf16, hipStream_t stream);
+hipError_t launch_combine(const void* y_perm, const int32_t* slot_row, const float* topk_w, int T, int k, int H,
+                          const void* y_shared, const void* x, const float* w_shared_gate, void* y_out,
+                          bool y_perm_bf16, bool out_f32, hipStream_t stream);
+
+}  // namespace moe

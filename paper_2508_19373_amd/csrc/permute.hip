@@ -1,0 +1,133 @@
+// Token permutation by expert: the dispatch step of the Top-K mechanism (paper, "MoE Model
+// Architectures"), restricted to the contiguous expert subset an expert-parallel shard holds
+// ("Expert Parallelism").  A stable counting sort of assignment ids a = t*k + j by expert id.
+//
+// Index kernel: one 1024-thread workgroup.  Pass 1 builds the per-expert histogram with LDS
+// integer atomics (order-independent result) and scans it.  Pass 2 walks the assignments in
+// order, 1024 at a time: inside a wavefront the rank among equal experts comes from ballot +
+// popcount, across the 16 wavefronts from a short serial prefix in LDS -- no order-dependent
+// atomics, so the result is the unique stable order and is identical from run to run.
+// Gather kernel: coalesced 16-byte-per-lane row copies x[row_src[r] / k] -> x_perm[r].
+#include "moe_internal.hpp"
+
+namespace moe {
+namespace {
+
+constexpr int kIdxThreads = 1024;
+constexpr int kIdxWaves = kIdxThreads / kWave;
+
+__global__ __launch_bounds__(kIdxThreads) void permute_index_kernel(const int32_t* __restrict__ topk_idx, int A,
+                                                                   int n_local, int offset,
+                                                                   int32_t* __restrict__ expert_offsets,
+                                                                   int32_t* __restrict__ row_src,
+                                                                   int32_t* __restrict__ slot_row) {
+  __shared__ int32_t base[MOE_MAX_EXPERTS];                   // next free row of each expert
+  __shared__ int32_t wave_cnt[kIdxWaves][MOE_MAX_EXPERTS];    // per-wave counts, then per-wave bases
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
+
+  for (int e = tid; e < n_local; e += kIdxThreads) base[e] = 0;
+  __syncthreads();
+  for (int a = tid; a < A; a += kIdxThreads) {
+    const int e = topk_idx[a] - offset;
+    if (e >= 0 && e < n_local) atomicAdd(&base[e], 1);
+  }
+  __syncthreads();
+  if (wv == 0) {  // exclusive scan of up to 256 counts by one wavefront, 64 at a time
+    int carry = 0;
+    for (int e0 = 0; e0 < n_local; e0 += kWave) {
+      const int e = e0 + lane;
+      const int c = (e < n_local) ? base[e] : 0;
+      int incl = c;
+#pragma unroll
+      for (int o = 1; o < kWave; o <<= 1) {
+        const int v = __shfl_up(incl, o, kWave);
+        if (lane >= o) incl += v;
+      }
+      if (e < n_local) {
+        base[e] = carry + incl - c;
+        expert_offsets[e] = carry + incl - c;
+      }
+      carry += __shfl(incl, kWave - 1, kWave);
+    }
+    if (lane == 0) expert_offsets[n_local] = carry;
+  }
+  __syncthreads();
+
+  for (int a0 = 0; a0 < A; a0 += kIdxThreads) {
+    for (int i = tid; i < kIdxWaves * n_local; i += kIdxThreads) wave_cnt[i / n_local][i % n_local] = 0;
+    __syncthreads();
+    const int a = a0 + tid;
+    int e = -1;
+    if (a < A) {
+      e = topk_idx[a] - offset;
+      if (e < 0 || e >= n_local) e = -1;
+    }
+    int rank = 0;
+    unsigned long long todo = __ballot(e >= 0);
+    while (todo) {
+      const int leader = __ffsll((long long)todo) - 1;
+      const int le = __shfl(e, leader, kWave);
+      const unsigned long long m = __ballot(e == le);
+      if (e == le) rank = __popcll(m & ((1ull << lane) - 1ull));
+      if (lane == leader) wave_cnt[wv][le] = __popcll(m);
+      todo &= ~m;
+    }
+    __syncthreads();
+    for (int ee = tid; ee < n_local; ee += kIdxThreads) {
+      int run = base[ee];
+#pragma unroll
+      for (int w = 0; w < kIdxWaves; ++w) {
+        const int c = wave_cnt[w][ee];
+        wave_cnt[w][ee] = run;
+        run += c;
+      }
+      base[ee] = run;
+    }
+    __syncthreads();
+    if (a < A) {
+      if (e >= 0) {
+        const int row = wave_cnt[wv][e] + rank;
+        slot_row[a] = row;
+        row_src[row] = a;
+      } else {
+        slot_row[a] = -1;
+      }
+    }
+    __syncthreads();
+  }
+}
+
+constexpr int kGatherThreads = 256;
+
+__global__ __launch_bounds__(kGatherThreads) void gather_rows_kernel(const uint4* __restrict__ x,
+                                                                    const int32_t* __restrict__ row_src,
+                                                                    const int32_t* __restrict__ expert_offsets,
+                                                                    int n_local, int k, int chunks_per_row,
+                                                                    uint4* __restrict__ x_perm) {
+  const int R = expert_offsets[n_local];
+  for (int r = blockIdx.x; r < R; r += gridDim.x) {
+    const int tok = row_src[r] / k;
+    const uint4* src = x + (size_t)tok * chunks_per_row;
+    uint4* dst = x_perm + (size_t)r * chunks_per_row;
+    for (int c = threadIdx.x; c < chunks_per_row; c += kGatherThreads) dst[c] = src[c];
+  }
+}
+
+}  // namespace
+
+hipError_t launch_permute(const void* x, const int32_t* topk_idx, int T, int k, int H, int n_local, int offset,
+                          void* x_perm, int32_t* expert_offsets, int32_t* row_src, int32_t* slot_row,
+                          hipStream_t stream) {
+  const int A = T * k;
+  hipLaunchKernelGGL(permute_index_kernel, dim3(1), dim3(kIdxThreads), 0, stream, topk_idx, A, n_local, offset,
+                     expert_offsets, row_src, slot_row);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess || A == 0) return err;
+  const int grid = A < 8192 ? A : 8192;
+  hipLaunchKernelGGL(gather_rows_kernel, dim3(grid), dim3(kGatherThreads), 0, stream,
+                     static_cast<const uint4*>(x), row_src, expert_offsets, n_local, k, H / 8,
+                     static_cast<uint4*>(x_perm));
+  return hipGetLastError();
+}
+
+}  // namespace moe

@@ -1,0 +1,112 @@
+"""One Expert-module call on one shard: owns the device buffers (allocated once through torch)
+and issues the C-ABI calls in order.  No arithmetic happens here."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def bf16_tensor(bits: np.ndarray, device="cuda") -> torch.Tensor:
+    """uint16 bf16 bit patterns (numpy) -> torch.bfloat16 tensor on the device, same bits."""
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device).view(torch.bfloat16)
+
+
+def bf16_bits(t: torch.Tensor) -> np.ndarray:
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+class ExpertShardLayer:
+    """route -> permute -> expert FFN (-> shared expert FFN) -> combine, on the current stream.
+
+    Weights are torch.bfloat16 CUDA tensors in the layouts of include/moe_shard.h.
+    ``y_perm_bf16`` / ``out_f32`` select the element types of the intermediate and the output.
+    """
+
+    def __init__(self, *, n_experts, top_k, hidden, inter_full, inter_slice, n_local_experts=None, expert_offset=0,
+                 renorm=True, w_router=None, w_gate=None, w_up=None, w_down=None, shared=None, w_shared_gate=None,
+                 inter_shared_full=0, inter_shared_slice=0, max_tokens=0, y_perm_bf16=False, out_f32=False,
+                 device="cuda"):
+        n_local_experts = n_experts if n_local_experts is None else n_local_experts
+        self.E, self.k, self.H = n_experts, top_k, hidden
+        self.shard = B.make_shard(n_experts, n_local_experts, expert_offset, hidden, inter_full, inter_slice)
+        self.renorm = renorm
+        self.w_router, self.w_gate, self.w_up, self.w_down = w_router, w_gate, w_up, w_down
+        self.shared, self.w_shared_gate = shared, w_shared_gate
+        self.shared_shard = None
+        if shared is not None:
+            self.shared_shard = B.make_shard(1, 1, 0, hidden, inter_shared_full, inter_shared_slice)
+        self.y_perm_bf16, self.out_f32 = y_perm_bf16, out_f32
+        self.device = device
+        self.Tmax = -1
+        if max_tokens:
+            self._alloc(max_tokens)
+
+    def _alloc(self, T):
+        d, k, H, E = self.device, self.k, self.H, self.E
+        cap = max(T * k, 1)
+        Tn = max(T, 1)
+        ydt = torch.bfloat16 if self.y_perm_bf16 else torch.float32
+        self.logits = torch.empty((Tn, E), dtype=torch.float32, device=d)
+        self.topk_idx = torch.empty((Tn, k), dtype=torch.int32, device=d)
+        self.topk_w = torch.empty((Tn, k), dtype=torch.float32, device=d)
+        self.x_perm = torch.empty((cap, H), dtype=torch.bfloat16, device=d)
+        self.expert_offsets = torch.empty(self.shard.n_local_experts + 1, dtype=torch.int32, device=d)
+        self.row_src = torch.empty(cap, dtype=torch.int32, device=d)
+        self.slot_row = torch.empty(cap, dtype=torch.int32, device=d)
+        self.h_ws = torch.empty((cap, self.shard.inter_slice), dtype=torch.bfloat16, device=d)
+        self.y_perm = torch.empty((cap, H), dtype=ydt, device=d)
+        self.workspace = torch.empty(max(B.moe_workspace_bytes(T, k, self.shard), 256), dtype=torch.uint8, device=d)
+        self.y_out = torch.empty((Tn, H), dtype=torch.float32 if self.out_f32 else torch.bfloat16, device=d)
+        if self.shared is not None:
+            self.sh_offsets = torch.zeros(2, dtype=torch.int32, device=d)
+            self.h_sh = torch.empty((Tn, self.shared_shard.inter_slice), dtype=torch.bfloat16, device=d)
+            self.y_shared = torch.empty((Tn, H), dtype=ydt, device=d)
+        self.Tmax = T
+
+    def forward(self, x: torch.Tensor, logits: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+        T = x.shape[0]
+        if T > self.Tmax:
+            self._alloc(T)
+        k, H, E = self.k, self.H, self.E
+        flags = B.MOE_RENORM_TOPK if self.renorm else 0
+        if logits is not None:
+            self.logits[:T].copy_(logits)
+            flags |= B.MOE_LOGITS_GIVEN
+        B.moe_route_topk(x, self.w_router, self.logits, T, H, E, k, flags, self.topk_idx, self.topk_w, stream)
+        B.moe_permute(x, self.topk_idx, T, k, self.shard, self.x_perm, self.expert_offsets, self.row_src,
+                      self.slot_row, self.workspace, stream=stream)
+        yflag = B.MOE_Y_PERM_BF16 if self.y_perm_bf16 else 0
+        B.moe_expert_ffn(self.x_perm, self.expert_offsets, T * k, self.shard, self.w_gate, self.w_up, self.w_down,
+                         self.h_ws, self.y_perm, yflag, stream)
+        y_shared = None
+        if self.shared is not None:
+            if getattr(self, "_sh_T", None) != T:
+                self.sh_offsets.copy_(torch.tensor([0, T], dtype=torch.int32))
+                self._sh_T = T
+            B.moe_expert_ffn(x, self.sh_offsets, T, self.shared_shard, self.shared[0], self.shared[1], self.shared[2],
+                             self.h_sh, self.y_shared, yflag, stream)
+            y_shared = self.y_shared
+        cflags = yflag | (B.MOE_OUT_F32 if self.out_f32 else 0)
+        gate_x = x if self.w_shared_gate is not None else None
+        B.moe_combine(self.y_perm, self.slot_row, self.topk_w, T, k, H, y_shared, gate_x, self.w_shared_gate,
+                      self.y_out, cflags, stream)
+        return self.y_out[:T]
+
+    @classmethod
+    def from_inputs(cls, li, **kw) -> "ExpertShardLayer":
+        """Build from paper_2508_19373_amd.inputs.LayerInputs (uploads the weights)."""
+        s = li.shape
+        shared = None
+        if li.ws_gate is not None:
+            shared = tuple(bf16_tensor(w) for w in (li.ws_gate, li.ws_up, li.ws_down))
+        return cls(n_experts=s.n_experts, top_k=s.top_k, hidden=s.hidden, inter_full=s.inter,
+                   inter_slice=s.inter_slice, n_local_experts=s.n_local_experts, expert_offset=s.expert_offset,
+                   renorm=s.renorm,
+                   w_router=None if li.w_router is None else torch.from_numpy(li.w_router).cuda(),
+                   w_gate=bf16_tensor(li.w_gate), w_up=bf16_tensor(li.w_up), w_down=bf16_tensor(li.w_down),
+                   shared=shared,
+                   w_shared_gate=None if (li.w_shared_gate is None or shared is None) else torch.from_numpy(li.w_shared_gate).cuda(),
+                   inter_shared_full=s.inter_shared, inter_shared_slice=s.inter_shared_slice,
+                   max_tokens=li.T, **kw)

@@ -1,0 +1,128 @@
+"""The C-ABI library loads without a GPU, exports every symbol the header declares, and
+rejects invalid arguments on the host before any device call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2508_19373_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B._LIB_PATH):
+        import __graft_entry__ as g
+        g.build()
+    return B.lib()
+
+
+def _declared_functions():
+    src = open(os.path.join(ROOT, "include", "moe_shard.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_header_constants_match_binding():
+    src = open(os.path.join(ROOT, "include", "moe_shard.h")).read()
+    for name in ("MOE_ERR_INVALID_ARG", "MOE_ERR_UNSUPPORTED_SHAPE", "MOE_ERR_WORKSPACE", "MOE_ERR_HIP"):
+        m = re.search(name + r"\s*=\s*(-?\d+)", src)
+        assert int(m.group(1)) == getattr(B, name)
+    for name in ("MOE_RENORM_TOPK", "MOE_LOGITS_GIVEN", "MOE_Y_PERM_BF16", "MOE_OUT_F32"):
+        m = re.search(name + r"\s*=\s*1u\s*<<\s*(\d+)", src)
+        assert 1 << int(m.group(1)) == getattr(B, name)
+    assert ctypes.sizeof(B.MoeShard) == 24
+
+
+def test_status_strings(lib):
+    assert B.status_string(0) == "ok"
+    for s in (-1, -2, -3, -4):
+        assert B.status_string(s) not in ("ok", "unknown status")
+    assert B.status_string(-99) == "unknown status"
+
+
+P = 0x1000  # a fake, aligned, non-null "device pointer": validation must fail before it is touched
+
+
+def test_route_topk_validation(lib):
+    f = lib.moe_route_topk
+    assert f(P, P, P, 4, 64, 8, 0, 0, P, P, None) == B.MOE_ERR_INVALID_ARG       # k < 1
+    assert f(P, P, P, 4, 64, 8, 9, 0, P, P, None) == B.MOE_ERR_INVALID_ARG       # k > E
+    assert f(P, P, P, 4, 64, 300, 2, 0, P, P, None) == B.MOE_ERR_INVALID_ARG     # E too large
+    assert f(P, P, P, -1, 64, 8, 2, 0, P, P, None) == B.MOE_ERR_INVALID_ARG      # T < 0
+    assert f(None, P, P, 4, 64, 8, 2, 0, P, P, None) == B.MOE_ERR_INVALID_ARG    # x missing
+    assert f(P, P, None, 4, 64, 8, 2, 0, P, P, None) == B.MOE_ERR_INVALID_ARG    # logits missing
+    assert f(P, P, P, 4, 60, 8, 2, 0, P, P, None) == B.MOE_ERR_UNSUPPORTED_SHAPE  # H % 8
+    assert f(P, P, P, 4, 64, 8, 2, 1 << 7, P, P, None) == B.MOE_ERR_INVALID_ARG  # unknown flag
+    assert f(P + 2, P, P, 4, 64, 8, 2, 0, P, P, None) == B.MOE_ERR_INVALID_ARG   # misaligned x
+
+
+def _shard(**kw):
+    d = dict(n_experts=8, n_local_experts=8, expert_offset=0, hidden=512, inter_full=1024, inter_slice=1024)
+    d.update(kw)
+    return B.MoeShard(**d)
+
+
+@pytest.mark.parametrize("bad", [
+    dict(n_local_experts=0), dict(n_local_experts=3), dict(expert_offset=-1),
+    dict(n_local_experts=4, expert_offset=6), dict(inter_slice=300), dict(inter_slice=2048),
+    dict(n_experts=0), dict(n_experts=512, n_local_experts=512), dict(hidden=0),
+])
+def test_shard_descriptor_validation(lib, bad):
+    s = _shard(**bad)
+    assert B.moe_workspace_bytes(4, 2, s) == 0
+    assert lib.moe_permute(P, P, 4, 2, ctypes.byref(s), P, P, P, P, P, 1024, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_expert_ffn(P, P, 8, ctypes.byref(s), P, P, P, P, P, 0, None) == B.MOE_ERR_INVALID_ARG
+
+
+def test_permute_validation(lib):
+    s = _shard()
+    need = B.moe_workspace_bytes(4, 2, s)
+    assert need > 0
+    f = lib.moe_permute
+    assert f(P, P, 4, 2, None, P, P, P, P, P, need, None) == B.MOE_ERR_INVALID_ARG
+    assert f(P, P, 4, 2, ctypes.byref(s), P, P, P, P, P, need - 1, None) == B.MOE_ERR_WORKSPACE
+    assert f(P, P, 4, 2, ctypes.byref(s), P, P, P, P, None, need, None) == B.MOE_ERR_WORKSPACE
+    assert f(P, None, 4, 2, ctypes.byref(s), P, P, P, P, P, need, None) == B.MOE_ERR_INVALID_ARG
+    assert f(P, P, 4, 17, ctypes.byref(s), P, P, P, P, P, need, None) == B.MOE_ERR_INVALID_ARG
+    assert f(P, P, 1 << 23, 2, ctypes.byref(s), P, P, P, P, P, need, None) == B.MOE_ERR_INVALID_ARG
+    s2 = _shard(hidden=12)
+    assert f(P, P, 4, 2, ctypes.byref(s2), P, P, P, P, P, need, None) == B.MOE_ERR_UNSUPPORTED_SHAPE
+
+
+def test_expert_ffn_validation(lib):
+    f = lib.moe_expert_ffn
+    s = _shard()
+    assert f(P, P, -1, ctypes.byref(s), P, P, P, P, P, 0, None) == B.MOE_ERR_INVALID_ARG
+    assert f(P, P, 8, ctypes.byref(s), P, None, P, P, P, 0, None) == B.MOE_ERR_INVALID_ARG
+    assert f(P, P, 8, ctypes.byref(s), P, P, P, P, P, B.MOE_OUT_F32, None) == B.MOE_ERR_INVALID_ARG
+    assert f(P, P, 8, ctypes.byref(_shard(hidden=520)), P, P, P, P, P, 0, None) == B.MOE_ERR_UNSUPPORTED_SHAPE
+    assert f(P, P, 8, ctypes.byref(_shard(inter_full=1000, inter_slice=500)), P, P, P, P, P, 0, None) \
+        == B.MOE_ERR_UNSUPPORTED_SHAPE
+    assert f(P, P, 8, ctypes.byref(s), P, P, P + 8, P, P, 0, None) == B.MOE_ERR_INVALID_ARG
+
+
+def test_combine_validation(lib):
+    f = lib.moe_combine
+    assert f(P, P, P, 4, 2, 512, None, None, None, None, 0, None) == B.MOE_ERR_INVALID_ARG
+    assert f(P, P, P, 4, 2, 512, P, P, None, P, 0, None) == B.MOE_ERR_INVALID_ARG   # x without w_s
+    assert f(P, P, P, 4, 2, 512, None, P, P, P, 0, None) == B.MOE_ERR_INVALID_ARG   # gate without y_shared
+    assert f(P, P, P, 4, 2, 510, None, None, None, P, 0, None) == B.MOE_ERR_UNSUPPORTED_SHAPE
+    assert f(P, P, P, 4, 0, 512, None, None, None, P, 0, None) == B.MOE_ERR_INVALID_ARG
+    assert f(P, P, P, 4, 2, 512, None, None, None, P, B.MOE_RENORM_TOPK, None) == B.MOE_ERR_INVALID_ARG
+
+
+def test_binding_refuses_host_tensors(lib):
+    import torch
+    t = torch.zeros(4, 8)
+    with pytest.raises(ValueError):
+        B.moe_route_topk(t, t, t, 4, 8, 8, 2, 0, t, t, stream=0)
