@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE Expert-module forward pass on one MI355X shard.
+
+A step is one pass of the whole hot path (route -> permute -> grouped SwiGLU FFN
+[-> shared expert] -> combine) over one batch of seeded synthetic input that is already
+resident in HBM.  Prints ONE JSON line: whole-layer throughput in bf16 TFLOP/s (algorithmic
+FLOPs only), ms per step, a roofline object for the dominant kernel measured live with
+events on the launch stream, and the CPU oracle timed on a bounded sample of the same
+workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload mixtral_prefill]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
+
+# name -> (inputs.WORKLOADS key, token count, description)
+WORKLOADS = {
+    "tiny": ("tiny", 64, "tiny 512/8e/top2/1024 T=64"),
+    "mixtral_prefill": ("mixtral", 4096, "mixtral-8x7b unsharded prefill T=4096"),
+    "mixtral_decode": ("mixtral", 16, "mixtral-8x7b unsharded decode T=16"),
+    "mixtral_tp4_prefill": ("mixtral_tp4", 8192, "mixtral-8x7b TP=4 shard T=8192"),
+    "mixtral_tp4_decode": ("mixtral_tp4", 64, "mixtral-8x7b TP=4 shard T=64"),
+    "mixtral_ep4_hot": ("mixtral_ep4_hot", 8192, "mixtral-8x7b EP=4 shard experts 0-1, Zipf(1.2), T=8192 global"),
+    "mixtral_ep4_cold": ("mixtral_ep4_cold", 8192, "mixtral-8x7b EP=4 shard experts 6-7, Zipf(1.2), T=8192 global"),
+    "qwen_prefill": ("qwen", 4096, "qwen1.5-moe-a2.7b + shared expert T=4096"),
+    "qwen_decode": ("qwen", 32, "qwen1.5-moe-a2.7b + shared expert T=32"),
+}
+
+
+def algorithmic_work(shape, T, counts):
+    """FLOPs and minimum HBM bytes the method itself needs for one layer on this shard
+    (never padded tiles, never inactive experts)."""
+    H, E, I_s = shape.hidden, shape.n_experts, shape.inter_slice
+    R = int(sum(counts))
+    active = int(sum(1 for c in counts if c > 0))
+    flops = 6.0 * R * H * I_s
+    if shape.router != "zipf":
+        flops += 2.0 * T * H * E
+    wbytes = 3.0 * H * I_s * 2 * active
+    if shape.inter_shared:
+        flops += 6.0 * T * H * shape.inter_shared_slice + 2.0 * T * H
+        wbytes += 3.0 * H * shape.inter_shared_slice * 2
+    bytes_ = wbytes + H * E * 4 + 2.0 * T * H * 2
+    return flops, bytes_, R, active
+
+
+def time_events(fn, iters, torch):
+    """Average duration (ms) of fn() over `iters` back-to-back launches, from events recorded
+    on the stream the kernels are launched on (torch's current stream)."""
+    start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(iters):
+        fn()
+    end.record()
+    end.synchronize()
+    return start.elapsed_time(end) / iters
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="mixtral_prefill", choices=sorted(WORKLOADS))
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens the oracle is timed on (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU's shard: this build has no multi-GPU path; run with --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2508_19373_amd import binding as B
+    from paper_2508_19373_amd import inputs as I
+    from paper_2508_19373_amd.layer import ExpertShardLayer, bf16_tensor
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    B.lib()  # fail loudly when the HIP library is missing
+    torch.cuda.set_device(0)
+
+    key, T, desc = WORKLOADS[args.workload]
+    shape, _ = I.WORKLOADS[key]
+    t0 = time.time()
+    li = I.make_layer_inputs(shape, T, args.seed)
+    gen_s = time.time() - t0
+    layer = ExpertShardLayer.from_inputs(li)
+    x = bf16_tensor(li.x)
+    logits = None if li.logits is None else torch.from_numpy(li.logits).cuda()
+
+    def step():
+        return layer.forward(x, logits)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    counts = np.diff(layer.expert_offsets.cpu().numpy())
+    flops, min_bytes, R, active = algorithmic_work(shape, T, counts)
+    tflops = flops / (ms_per_step * 1e-3) / 1e12
+    gbs = min_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---- per-call breakdown and the dominant kernel, events on the launch stream
+    k, H, E = shape.top_k, shape.hidden, shape.n_experts
+    rflags = (B.MOE_RENORM_TOPK if shape.renorm else 0) | (B.MOE_LOGITS_GIVEN if logits is not None else 0)
+    it = max(5, args.steps)
+    br = {}
+    br["route_topk"] = time_events(lambda: B.moe_route_topk(x, layer.w_router, layer.logits, T, H, E, k, rflags,
+                                                            layer.topk_idx, layer.topk_w), it, torch)
+    br["permute"] = time_events(lambda: B.moe_permute(x, layer.topk_idx, T, k, layer.shard, layer.x_perm,
+                                                      layer.expert_offsets, layer.row_src, layer.slot_row,
+                                                      layer.workspace), it, torch)
+    ffn = lambda fl: B.moe_expert_ffn(layer.x_perm, layer.expert_offsets, T * k, layer.shard, layer.w_gate,
+                                      layer.w_up, layer.w_down, layer.h_ws, layer.y_perm, fl)
+    br["ffn_gateup_swiglu"] = time_events(lambda: ffn(B.MOE_FFN_SKIP_DOWN), it, torch)
+    br["ffn_down"] = time_events(lambda: ffn(B.MOE_FFN_SKIP_GATEUP), it, torch)
+    if layer.shared is not None:
+        br["shared_expert_ffn"] = time_events(
+            lambda: B.moe_expert_ffn(x, layer.sh_offsets, T, layer.shared_shard, *layer.shared, layer.h_sh,
+                                     layer.y_shared, 0), it, torch)
+    br["combine"] = time_events(
+        lambda: B.moe_combine(layer.y_perm, layer.slot_row, layer.topk_w, T, k, H,
+                              layer.y_shared if layer.shared is not None else None,
+                              x if layer.w_shared_gate is not None else None, layer.w_shared_gate, layer.y_out, 0),
+        it, torch)
+
+    # dominant kernel = GEMM1 (gate/up + SwiGLU): 2/3 of the routed FLOPs, 2/3 of the weight bytes
+    g1_ms = br["ffn_gateup_swiglu"]
+    I_s = shape.inter_slice
+    g1_flops = 4.0 * R * H * I_s
+    g1_bytes = 2.0 * active * H * I_s * 2 + R * H * 2 + R * I_s * 2
+    intensity = g1_flops / g1_bytes
+    if intensity > PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+        ach = g1_flops / (g1_ms * 1e-3) / 1e12
+        roofline = {"kernel": "grouped_gemm_kernel<GATEUP> (GEMM1 + SwiGLU)", "bound": "mfma", "achieved": ach,
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                    "ms": g1_ms, "flops_per_launch": g1_flops}
+    else:
+        ach = g1_bytes / (g1_ms * 1e-3) / 1e9
+        roofline = {"kernel": "grouped_gemm_kernel<GATEUP> (GEMM1 + SwiGLU)", "bound": "hbm", "achieved": ach,
+                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None,
+                    "ms": g1_ms, "bytes_per_launch": g1_bytes}
+
+    # ---- CPU baseline: the oracle as it stands on a bounded token sample
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import moe_oracle as O
+        n = args.cpu_sample_tokens or min(T, 32)
+        sel = np.linspace(0, T - 1, n).astype(np.int64)
+        lg = layer.logits[:T].cpu().numpy()[sel]
+        shared = (li.ws_gate, li.ws_up, li.ws_down) if li.ws_gate is not None else None
+        t0 = time.perf_counter()
+        ref = O.expert_layer(li.x[sel], lg, k, shape.renorm, shape.n_local_experts, shape.expert_offset, li.w_gate,
+                             li.w_up, li.w_down, shared=shared,
+                             w_shared_gate=li.w_shared_gate if shared else None)
+        cpu_s = time.perf_counter() - t0
+        idx_s, _, _ = O.route_topk(lg, k, shape.renorm)
+        cnt_s = [int(((idx_s >= shape.expert_offset + e) & (idx_s < shape.expert_offset + e + 1)).sum())
+                 for e in range(shape.n_local_experts)]
+        f_s, _, _, _ = algorithmic_work(shape, n, cnt_s)
+        got = layer.y_out[:T].float().cpu().numpy()[sel].astype(np.float64)
+        rel = float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30))
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count()
+        cpu = {"value": f_s / cpu_s / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+               "sample": "%d of %d tokens (evenly spaced), full weights, fp64 numpy; %.1f s" % (n, T, cpu_s),
+               "gpu_vs_oracle_rel_l2_on_sample": rel}
+
+    out = {
+        "metric": "moe_expert_layer_bf16_tflops", "value": tflops, "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "us_per_layer": ms_per_step * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": desc, "tokens": T, "routed_rows": R, "active_local_experts": active,
+                   "hidden": H, "n_experts": E, "top_k": k, "inter_slice": I_s,
+                   "n_local_experts": shape.n_local_experts, "expert_offset": shape.expert_offset, "seed": args.seed},
+        "pct_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS, "min_bytes_gbs": gbs,
+        "pct_hbm_peak": 100.0 * gbs / PEAK_HBM_GBS, "flops_per_layer": flops, "min_bytes_per_layer": min_bytes,
+        "breakdown_ms": br, "input_gen_s": gen_s, "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -47,7 +47,9 @@ enum {
   MOE_RENORM_TOPK = 1u << 0,  /* moe_route_topk: divide the k gate weights by their sum       */
   MOE_LOGITS_GIVEN = 1u << 1, /* moe_route_topk: `logits` is an input, x / w_router unused    */
   MOE_Y_PERM_BF16 = 1u << 2,  /* moe_expert_ffn / moe_combine: y_perm, y_shared are bf16 (default fp32) */
-  MOE_OUT_F32 = 1u << 3       /* moe_combine: y_out is fp32 (default bf16)                    */
+  MOE_OUT_F32 = 1u << 3,      /* moe_combine: y_out is fp32 (default bf16)                    */
+  MOE_FFN_SKIP_GATEUP = 1u << 4, /* moe_expert_ffn: do not run GEMM1; h_workspace is an input  */
+  MOE_FFN_SKIP_DOWN = 1u << 5    /* moe_expert_ffn: stop after GEMM1; y_perm is not written    */
 };
 
 /* limits of this implementation */
@@ -120,6 +122,8 @@ int moe_permute(const void* x_bf16, const int32_t* topk_idx, int32_t T, int32_t 
  * With inter_slice < inter_full, y_perm is the tensor-parallel partial sum.
  * The shared expert is a second call with n_local_experts = 1, expert_offsets = {0,T},
  * x_perm = x.  Requires H % 64 == 0, I_s % 64 == 0, cap_rows >= 0.
+ * MOE_FFN_SKIP_GATEUP / MOE_FFN_SKIP_DOWN run one of the two GEMMs alone (operator-level
+ * benchmarking, as the paper's latency model is fitted on measured operator latencies).
  */
 int moe_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int32_t cap_rows,
                    const moe_shard_t* shard, const void* w_gate, const void* w_up,

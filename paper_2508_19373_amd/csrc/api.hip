@@ -65,7 +65,8 @@ int moe_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int32_t ca
                    uint32_t flags, void* stream) {
   const int st = shard_status(shard);
   if (st != MOE_OK) return st;
-  if (cap_rows < 0 || (flags & ~(uint32_t)MOE_Y_PERM_BF16)) return MOE_ERR_INVALID_ARG;
+  if (cap_rows < 0 || (flags & ~(uint32_t)(MOE_Y_PERM_BF16 | MOE_FFN_SKIP_GATEUP | MOE_FFN_SKIP_DOWN)))
+    return MOE_ERR_INVALID_ARG;
   if (x_perm == nullptr || expert_offsets == nullptr || w_gate == nullptr || w_up == nullptr ||
       w_down == nullptr || h_workspace == nullptr || y_perm == nullptr)
     return MOE_ERR_INVALID_ARG;
@@ -75,7 +76,7 @@ int moe_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int32_t ca
     return MOE_ERR_INVALID_ARG;
   return hip_status(moe::launch_expert_ffn(x_perm, expert_offsets, cap_rows, shard->n_local_experts, shard->hidden,
                                            shard->inter_slice, w_gate, w_up, w_down, h_workspace, y_perm,
-                                           (flags & MOE_Y_PERM_BF16) != 0, static_cast<hipStream_t>(stream)));
+                                           flags, static_cast<hipStream_t>(stream)));
 }
 
 int moe_combine(const void* y_perm, const int32_t* slot_row, const float* topk_w, int32_t T, int32_t k, int32_t H,

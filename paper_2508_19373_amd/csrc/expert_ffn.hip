@@ -183,12 +183,13 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
 template <int BM, int BN, int WM, int WN>
 hipError_t launch_pair(const void* x_perm, const int32_t* expert_offsets, int cap_rows, int n_local, int H, int I_s,
                        const void* w_gate, const void* w_up, const void* w_down, void* h_ws, void* y_perm,
-                       bool y_bf16, hipStream_t stream) {
+                       uint32_t flags, hipStream_t stream) {
+  const bool y_bf16 = (flags & MOE_Y_PERM_BF16) != 0;
   const int m_blocks = cap_rows / BM + n_local;  // upper bound on sum_e ceil(rows_e / BM)
   const dim3 block(WM * WN * 64);
   const uint16_t* xp = static_cast<const uint16_t*>(x_perm);
   uint16_t* hw = static_cast<uint16_t*>(h_ws);
-  {
+  if (!(flags & MOE_FFN_SKIP_GATEUP)) {
     const dim3 grid((I_s + BN / 2 - 1) / (BN / 2), m_blocks);
     hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, WM, WN, true, uint16_t>), grid, block, 0, stream, xp,
                        expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_gate),
@@ -196,6 +197,7 @@ hipError_t launch_pair(const void* x_perm, const int32_t* expert_offsets, int ca
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
   }
+  if (flags & MOE_FFN_SKIP_DOWN) return hipSuccess;
   const dim3 grid((H + BN - 1) / BN, m_blocks);
   if (y_bf16)
     hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, WM, WN, false, uint16_t>), grid, block, 0, stream, hw,
@@ -212,10 +214,10 @@ hipError_t launch_pair(const void* x_perm, const int32_t* expert_offsets, int ca
 
 hipError_t launch_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int cap_rows, int n_local, int H,
                              int I_s, const void* w_gate, const void* w_up, const void* w_down, void* h_ws,
-                             void* y_perm, bool y_bf16, hipStream_t stream) {
+                             void* y_perm, uint32_t flags, hipStream_t stream) {
   if (cap_rows == 0) return hipSuccess;
   return launch_pair<128, 128, 2, 2>(x_perm, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,
-                                     y_perm, y_bf16, stream);
+                                     y_perm, flags, stream);
 }
 
 }  // namespace moe

@@ -98,6 +98,7 @@ class ExpertShardLayer:
     def from_inputs(cls, li, **kw) -> "ExpertShardLayer":
         """Build from paper_2508_19373_amd.inputs.LayerInputs (uploads the weights)."""
         s = li.shape
+        kw.setdefault("max_tokens", li.T)
         shared = None
         if li.ws_gate is not None:
             shared = tuple(bf16_tensor(w) for w in (li.ws_gate, li.ws_up, li.ws_down))
@@ -109,4 +110,4 @@ class ExpertShardLayer:
                    shared=shared,
                    w_shared_gate=None if (li.w_shared_gate is None or shared is None) else torch.from_numpy(li.w_shared_gate).cuda(),
                    inter_shared_full=s.inter_shared, inter_shared_slice=s.inter_shared_slice,
-                   max_tokens=li.T, **kw)
+                   **kw)

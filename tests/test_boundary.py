@@ -37,7 +37,8 @@ def test_header_constants_match_binding():
     for name in ("MOE_ERR_INVALID_ARG", "MOE_ERR_UNSUPPORTED_SHAPE", "MOE_ERR_WORKSPACE", "MOE_ERR_HIP"):
         m = re.search(name + r"\s*=\s*(-?\d+)", src)
         assert int(m.group(1)) == getattr(B, name)
-    for name in ("MOE_RENORM_TOPK", "MOE_LOGITS_GIVEN", "MOE_Y_PERM_BF16", "MOE_OUT_F32"):
+    for name in ("MOE_RENORM_TOPK", "MOE_LOGITS_GIVEN", "MOE_Y_PERM_BF16", "MOE_OUT_F32", "MOE_FFN_SKIP_GATEUP",
+                 "MOE_FFN_SKIP_DOWN"):
         m = re.search(name + r"\s*=\s*1u\s*<<\s*(\d+)", src)
         assert 1 << int(m.group(1)) == getattr(B, name)
     assert ctypes.sizeof(B.MoeShard) == 24

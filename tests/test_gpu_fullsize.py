@@ -1,0 +1,101 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+Integer outputs (top-k ids, offsets, permutation, permuted rows) are checked in full against
+the oracle; the layer output is checked on a random sample of tokens with every hidden column
+(each output row depends only on its own token, so a sample of rows is a valid check)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as O
+from paper_2508_19373_amd import binding as B
+from paper_2508_19373_amd import inputs as I
+from paper_2508_19373_amd.layer import ExpertShardLayer, bf16_bits, bf16_tensor
+
+pytestmark = pytest.mark.gpu
+
+REL_L2 = 5e-3
+MAX_ABS = 2e-2
+N_SAMPLE = 96
+
+CASES = [("mixtral", 16), ("mixtral", 4096), ("mixtral_tp4", 64), ("mixtral_tp4", 8192),
+         ("mixtral_ep4_hot", 8192), ("mixtral_ep4_cold", 8192), ("qwen", 32), ("qwen", 4096)]
+
+_cache = {}
+
+
+def _inputs(key, T):
+    # weights depend on the workload only; keep one workload's weights at a time
+    shape, _ = I.WORKLOADS[key]
+    if _cache.get("key") != key:
+        _cache.clear()
+        _cache["key"] = key
+        _cache["li"] = I.make_layer_inputs(shape, 1, 0)
+        _cache["layer"] = None
+    li = _cache["li"]
+    li.T = T
+    li.x = I.make_x(0, T, shape.hidden)
+    li.logits = I.make_zipf_logits(0, T, shape.n_experts) if shape.router == "zipf" else None
+    return shape, li
+
+
+def _ulp_bf16(v):
+    e = np.floor(np.log2(np.maximum(np.abs(v), 2.0 ** -126)))
+    return 2.0 ** (e - 7)
+
+
+@pytest.mark.parametrize("key,T", CASES)
+def test_full_size_against_oracle(key, T):
+    shape, li = _inputs(key, T)
+    k = shape.top_k
+    print("case", key, T, flush=True)
+    if _cache["layer"] is None:
+        _cache["layer"] = ExpertShardLayer.from_inputs(li, out_f32=True, max_tokens=8192 if "mixtral" in key else 4096)
+    layer = _cache["layer"]
+    x = bf16_tensor(li.x)
+    logits_in = None if li.logits is None else torch.from_numpy(li.logits).cuda()
+    y32 = layer.forward(x, logits_in).cpu().numpy().astype(np.float64)
+    ybf = torch.empty((T, shape.hidden), dtype=torch.bfloat16, device="cuda")
+    B.moe_combine(layer.y_perm, layer.slot_row, layer.topk_w, T, k, shape.hidden,
+                  layer.y_shared if layer.shared is not None else None,
+                  x if layer.w_shared_gate is not None else None, layer.w_shared_gate, ybf, 0)
+    torch.cuda.synchronize()
+    ybf = ybf.float().cpu().numpy().astype(np.float64)
+
+    # ---- integers, in full
+    logits = layer.logits[:T].cpu().numpy()
+    if li.logits is None:
+        ref_logits = O.router_logits(li.x, li.w_router).astype(np.float64)
+        assert np.all(np.abs(logits - ref_logits) <= 1e-5 * (1 + np.abs(ref_logits)))
+    else:
+        assert np.array_equal(logits, li.logits)
+    idx, w32, w64 = O.route_topk(logits, k, shape.renorm)
+    assert np.array_equal(layer.topk_idx[:T].cpu().numpy(), idx)
+    assert np.allclose(layer.topk_w[:T].cpu().numpy(), w32, rtol=2e-6, atol=1e-9)
+    offs, row_src, slot_row, x_perm = O.permute(li.x, idx, shape.n_local_experts, shape.expert_offset)
+    R = int(offs[-1])
+    assert np.array_equal(layer.expert_offsets.cpu().numpy(), offs)
+    assert np.array_equal(layer.row_src[:R].cpu().numpy(), row_src)
+    assert np.array_equal(layer.slot_row[:T * k].cpu().numpy(), slot_row)
+    assert np.array_equal(bf16_bits(layer.x_perm[:R]), x_perm)
+    if key == "mixtral_ep4_hot":
+        assert R > 0.5 * T * k  # experts 0,1 carry more than half of all rows under Zipf(1.2)
+    if key == "mixtral_ep4_cold":
+        assert R < 0.15 * T * k
+
+    # ---- floating point, on a token sample (GPU routing decisions, oracle arithmetic)
+    rng = np.random.default_rng(1)
+    sel = np.sort(rng.choice(T, size=min(T, N_SAMPLE), replace=False))
+    shared = (li.ws_gate, li.ws_up, li.ws_down) if li.ws_gate is not None else None
+    ref = O.expert_layer(li.x[sel], None, k, shape.renorm, shape.n_local_experts, shape.expert_offset, li.w_gate,
+                         li.w_up, li.w_down, shared=shared, w_shared_gate=li.w_shared_gate if shared else None,
+                         topk=(idx[sel], w64[sel]))
+    d32 = y32[sel] - ref
+    dbf = ybf[sel] - ref
+    rel32 = np.linalg.norm(d32) / np.linalg.norm(ref)
+    relbf = np.linalg.norm(dbf) / np.linalg.norm(ref)
+    print("  rel-L2 f32-out %.3e bf16-out %.3e | max-abs f32-out %.3e bf16-out %.3e (ref max %.2f)"
+          % (rel32, relbf, np.abs(d32).max(), np.abs(dbf).max(), np.abs(ref).max()), flush=True)
+    assert rel32 < REL_L2 and relbf < REL_L2
+    assert np.abs(d32).max() < MAX_ABS
+    # bf16 output: the format's own spacing reaches 2^-4 at |y| >= 8, so allow half an ulp on top
+    assert np.max(np.abs(dbf) - 0.5 * _ulp_bf16(ref)) < MAX_ABS
