@@ -72,8 +72,8 @@ def time_events(fn, iters, torch):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="mixtral_prefill", choices=sorted(WORKLOADS))
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -122,7 +122,7 @@ def main():
     # ---- per-call breakdown and the dominant kernel, events on the launch stream
     k, H, E = shape.top_k, shape.hidden, shape.n_experts
     rflags = (B.MOE_RENORM_TOPK if shape.renorm else 0) | (B.MOE_LOGITS_GIVEN if logits is not None else 0)
-    it = max(5, args.steps)
+    it = max(5, min(args.steps, 50))
     br = {}
     br["route_topk"] = time_events(lambda: B.moe_route_topk(x, layer.w_router, layer.logits, T, H, E, k, rflags,
                                                             layer.topk_idx, layer.topk_w), it, torch)

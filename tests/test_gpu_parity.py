@@ -153,6 +153,8 @@ def _ffn_gpu(x_perm_bits, offs, shard, wg, wu, wd, y_bf16=False):
     (64, 64, [5]),
     (256, 192, [300, 129]),
     (2048, 704, [3, 0, 9, 1]),
+    (320, 448, [700, 0, 300, 257, 1]),               # large groups: the 256x256 LDS-DMA kernel, ragged everywhere
+    (512, 1024, [256, 512]),                         # exact multiples of the tile
 ])
 def test_expert_ffn_against_oracle(H, I_s, counts):
     n = len(counts)
