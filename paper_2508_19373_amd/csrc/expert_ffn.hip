@@ -211,21 +211,21 @@ hipError_t launch_pair(const void* x_perm, const int32_t* expert_offsets, int ca
   return hipGetLastError();
 }
 
-// Prefill-sized groups: LDS-DMA kernel, 256x256 tiles, 4 wavefronts of 128x128 each.
-template <int BM, int BN, int WM, int WN>
+// Prefill-sized groups: LDS-DMA kernel, 256-column tiles of 256 / 128 / 64 rows.
+template <int BN>
 hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, int cap_rows, int n_local, int H,
                             int I_s, const void* w_gate, const void* w_up, const void* w_down, void* h_ws,
                             void* y_perm, uint32_t flags, hipStream_t stream) {
   const bool y_bf16 = (flags & MOE_Y_PERM_BF16) != 0;
-  const int m_blocks = cap_rows / BM + n_local;  // upper bound on sum_e ceil(rows_e / BM)
-  const dim3 block(WM * WN * 64);
+  const int m_blocks = gg::max_row_blocks(cap_rows, n_local);
+  const dim3 block(256);
   const uint16_t* xp = static_cast<const uint16_t*>(x_perm);
   uint16_t* hw = static_cast<uint16_t*>(h_ws);
   auto grid_for = [&](int ncb) { return dim3((unsigned)((ncb * m_blocks + gg::kNumXcd - 1) / gg::kNumXcd * gg::kNumXcd)); };
   if (!(flags & MOE_FFN_SKIP_GATEUP)) {
     const int ncb = (I_s + BN / 2 - 1) / (BN / 2);
-    hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BM, BN, WM, WN, true, uint16_t>), grid_for(ncb), block, 0,
-                       stream, xp, expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_gate),
+    hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, true, uint16_t>), grid_for(ncb), block, 0, stream, xp,
+                       expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_gate),
                        static_cast<const uint16_t*>(w_up), I_s, H, hw, ncb);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
@@ -233,12 +233,12 @@ hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, i
   if (flags & MOE_FFN_SKIP_DOWN) return hipSuccess;
   const int ncb = (H + BN - 1) / BN;
   if (y_bf16)
-    hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BM, BN, WM, WN, false, uint16_t>), grid_for(ncb), block, 0,
-                       stream, hw, expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_down),
+    hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, uint16_t>), grid_for(ncb), block, 0, stream, hw,
+                       expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_down),
                        static_cast<const uint16_t*>(nullptr), H, I_s, static_cast<uint16_t*>(y_perm), ncb);
   else
-    hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BM, BN, WM, WN, false, float>), grid_for(ncb), block, 0, stream,
-                       hw, expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_down),
+    hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, float>), grid_for(ncb), block, 0, stream, hw,
+                       expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_down),
                        static_cast<const uint16_t*>(nullptr), H, I_s, static_cast<float*>(y_perm), ncb);
   return hipGetLastError();
 }
@@ -251,8 +251,8 @@ hipError_t launch_expert_ffn(const void* x_perm, const int32_t* expert_offsets, 
   if (cap_rows == 0) return hipSuccess;
   // Average rows per local expert decides the tile height: large groups take the 256x256
   // LDS-DMA kernel, small ones the 128x128 register-staged kernel.
-  if (cap_rows / n_local >= 192)
-    return launch_pair_dlds<256, 256, 2, 2>(x_perm, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down,
+  if (cap_rows / n_local >= 48)
+    return launch_pair_dlds<256>(x_perm, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down,
                                             h_ws, y_perm, flags, stream);
   return launch_pair<128, 128, 2, 2>(x_perm, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,
                                      y_perm, flags, stream);

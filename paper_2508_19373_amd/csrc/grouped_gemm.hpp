@@ -57,24 +57,39 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
+// Row blocks of one expert: as many 256-row blocks as fit, then the remainder r is covered by
+// the cheapest of {64}, {128}, {128 + 64}, {256} rows, so the padding per expert is below 64
+// rows (padded rows are pure loss: only algorithmic FLOPs count).
+struct RowBlocks {
+  int n256, n128, n64;
+  __device__ __forceinline__ int total() const { return n256 + n128 + n64; }
+};
+__device__ __forceinline__ RowBlocks row_blocks(int rows) {
+  RowBlocks rb;
+  const int r = rows & 255;
+  rb.n256 = (rows >> 8) + (r > 192 ? 1 : 0);
+  rb.n128 = (r > 64 && r <= 192) ? 1 : 0;
+  rb.n64 = ((r > 0 && r <= 64) || (r > 128 && r <= 192)) ? 1 : 0;
+  return rb;
+}
+// Host-side upper bound on sum_e row_blocks(rows_e).total() given sum_e rows_e <= cap_rows.
+inline int max_row_blocks(int cap_rows, int n_local) { return cap_rows / 256 + 2 * n_local; }
+
 struct TileCoord {
-  int expert, row0, row_end, nb;
+  int expert, row0, row_end, nb, height;  // height: 256, 128 or 64
   bool valid;
 };
 
 // Tile `lid` of the list: experts in order, inside an expert column blocks in order, inside a
 // column block the row blocks (row block fastest, so neighbours share the B panel and a run of
 // tiles covers all row blocks of a few column blocks).
-template <int BM>
 __device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ expert_offsets, int n_local,
-                                               int n_col_blocks, int bid, int n_blocks_launched) {
+                                               int n_col_blocks, int bid) {
   TileCoord t;
   t.valid = false;
   int total = 0;
-  for (int e = 0; e < n_local; ++e) {
-    const int rows = expert_offsets[e + 1] - expert_offsets[e];
-    total += ((rows + BM - 1) / BM) * n_col_blocks;
-  }
+  for (int e = 0; e < n_local; ++e)
+    total += row_blocks(expert_offsets[e + 1] - expert_offsets[e]).total() * n_col_blocks;
   // XCD remap: workgroup b runs on XCD b % 8; give XCD x the tiles [x*chunk, (x+1)*chunk)
   const int chunk = (total + kNumXcd - 1) / kNumXcd;
   const int xcd = bid % kNumXcd, slot = bid / kNumXcd;
@@ -83,13 +98,24 @@ __device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ exper
   if (lid >= total) return t;
   for (int e = 0; e < n_local; ++e) {
     const int lo = expert_offsets[e], hi = expert_offsets[e + 1];
-    const int mbs = (hi - lo + BM - 1) / BM;
+    const RowBlocks rb = row_blocks(hi - lo);
+    const int mbs = rb.total();
     const int tiles = mbs * n_col_blocks;
     if (lid < tiles) {
+      const int mi = lid % mbs;
       t.expert = e;
       t.nb = lid / mbs;
-      t.row0 = lo + (lid % mbs) * BM;
       t.row_end = hi;
+      if (mi < rb.n256) {
+        t.height = 256;
+        t.row0 = lo + mi * 256;
+      } else if (mi < rb.n256 + rb.n128) {
+        t.height = 128;
+        t.row0 = lo + rb.n256 * 256;
+      } else {
+        t.height = 64;
+        t.row0 = lo + rb.n256 * 256 + rb.n128 * 128;
+      }
       t.valid = true;
       return t;
     }
@@ -98,11 +124,12 @@ __device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ exper
   return t;
 }
 
+// One (BM x BN) output tile, computed by the whole workgroup of WM x WN wavefronts.
 template <int BM, int BN, int WM, int WN, bool GATEUP, typename OutT>
-__global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_dlds_kernel(
-    const uint16_t* __restrict__ A, const int32_t* __restrict__ expert_offsets, int n_local, int cap_rows,
-    const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1, int n_out, int K, OutT* __restrict__ C,
-    int n_col_blocks) {
+__device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, const uint16_t* __restrict__ A,
+                                          int cap_rows, const uint16_t* __restrict__ B0,
+                                          const uint16_t* __restrict__ B1, int n_out, int K,
+                                          OutT* __restrict__ C) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int A_INST = BM / 8 / NW, B_INST = BN / 8 / NW;  // DMA instructions per wave per k-tile
@@ -111,11 +138,6 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_dlds_kernel(
   static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "tile / wave grid mismatch");
   static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "loader mismatch");
   static_assert(!GATEUP || (TN % 2 == 0), "gate and up column blocks must pair up inside a wave");
-
-  __shared__ __attribute__((aligned(1024))) uint16_t smem[2 * STAGE];
-
-  const TileCoord tc = find_tile<BM>(expert_offsets, n_local, n_col_blocks, blockIdx.x, gridDim.x);
-  if (!tc.valid) return;
   const int row0 = tc.row0, hi = tc.row_end, col0 = tc.nb * NCOLS;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -315,6 +337,24 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_dlds_kernel(
     store_tile([](int, int) { return true; });
   else
     store_tile([&](int row, int col) { return row < hi && col < n_out; });
+}
+
+// Kernel: 256 threads (4 wavefronts); each workgroup computes one tile of the list, whose
+// height (256, 128 or 64 rows) selects the wave arrangement.
+template <int BN, bool GATEUP, typename OutT>
+__global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
+    const uint16_t* __restrict__ A, const int32_t* __restrict__ expert_offsets, int n_local, int cap_rows,
+    const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1, int n_out, int K, OutT* __restrict__ C,
+    int n_col_blocks) {
+  __shared__ __attribute__((aligned(1024))) uint16_t smem[2 * (256 + BN) * BK];
+  const TileCoord tc = find_tile(expert_offsets, n_local, n_col_blocks, blockIdx.x);
+  if (!tc.valid) return;
+  if (tc.height == 256)
+    gemm_tile<256, BN, 2, 2, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, C);
+  else if (tc.height == 128)
+    gemm_tile<128, BN, 2, 2, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, C);
+  else
+    gemm_tile<64, BN, 1, 4, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, C);
 }
 
 }  // namespace gg
