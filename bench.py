@@ -130,13 +130,13 @@ def main():
                                                       layer.expert_offsets, layer.row_src, layer.slot_row,
                                                       layer.workspace), it, torch)
     ffn = lambda fl: B.moe_expert_ffn(layer.x_perm, layer.expert_offsets, T * k, layer.shard, layer.w_gate,
-                                      layer.w_up, layer.w_down, layer.h_ws, layer.y_perm, fl)
+                                      layer.w_up, layer.w_down, layer.h_ws, layer.y_perm, layer.ffn_ws, fl)
     br["ffn_gateup_swiglu"] = time_events(lambda: ffn(B.MOE_FFN_SKIP_DOWN), it, torch)
     br["ffn_down"] = time_events(lambda: ffn(B.MOE_FFN_SKIP_GATEUP), it, torch)
     if layer.shared is not None:
         br["shared_expert_ffn"] = time_events(
             lambda: B.moe_expert_ffn(x, layer.sh_offsets, T, layer.shared_shard, *layer.shared, layer.h_sh,
-                                     layer.y_shared, 0), it, torch)
+                                     layer.y_shared, layer.ffn_ws_sh, 0), it, torch)
     br["combine"] = time_events(
         lambda: B.moe_combine(layer.y_perm, layer.slot_row, layer.topk_w, T, k, H,
                               layer.y_shared if layer.shared is not None else None,

@@ -117,7 +117,9 @@ int moe_permute(const void* x_bf16, const int32_t* topk_idx, int32_t T, int32_t 
  * expert_offsets [E_loc+1] int32 (device), non-decreasing, last <= cap_rows
  * w_gate, w_up   [E_loc][I_s][H] bf16   (row = output feature, H contiguous)
  * w_down         [E_loc][H][I_s] bf16   (row = output feature, I_s contiguous)
- * h_workspace    [cap_rows,I_s] bf16    scratch for h
+ * h_workspace    [cap_rows,I_s] bf16    the activated intermediate h (output of GEMM1)
+ * workspace      at least moe_ffn_workspace_bytes(cap_rows, shard) bytes, 256-byte aligned
+ *                (split-K partial sums of the decode path); may be NULL when that is 0
  * y_perm         [cap_rows,H] fp32 (bf16 with MOE_Y_PERM_BF16); rows [0,R) written
  * With inter_slice < inter_full, y_perm is the tensor-parallel partial sum.
  * The shared expert is a second call with n_local_experts = 1, expert_offsets = {0,T},
@@ -128,7 +130,7 @@ int moe_permute(const void* x_bf16, const int32_t* topk_idx, int32_t T, int32_t 
 int moe_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int32_t cap_rows,
                    const moe_shard_t* shard, const void* w_gate, const void* w_up,
                    const void* w_down, void* h_workspace, void* y_perm,
-                   uint32_t flags, void* stream);
+                   void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
 
 /*
  * Weighted un-permute / combine of the Top-K expert outputs, plus the shared expert:
@@ -149,6 +151,9 @@ int moe_combine(const void* y_perm, const int32_t* slot_row, const float* topk_w
 
 /* Bytes of scratch moe_permute needs for (T, k, shard); 0 on invalid arguments. */
 size_t moe_workspace_bytes(int32_t T, int32_t k, const moe_shard_t* shard);
+
+/* Bytes of scratch moe_expert_ffn needs for (cap_rows, shard); 0 if none (or invalid arguments). */
+size_t moe_ffn_workspace_bytes(int32_t cap_rows, const moe_shard_t* shard);
 
 /* Static, NUL-terminated description of a status code. */
 const char* moe_status_string(int status);

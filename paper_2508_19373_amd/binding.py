@@ -26,7 +26,7 @@ MOE_MAX_EXPERTS = 256
 MOE_MAX_TOPK = 16
 
 EXPORTS = ("moe_route_topk", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_workspace_bytes",
-           "moe_status_string")
+           "moe_ffn_workspace_bytes", "moe_status_string")
 
 
 class MoeShard(ctypes.Structure):
@@ -54,12 +54,14 @@ def lib() -> ctypes.CDLL:
         L.moe_route_topk.restype = ctypes.c_int
         L.moe_permute.argtypes = [vp, vp, i32, i32, shp, vp, vp, vp, vp, vp, sz, vp]
         L.moe_permute.restype = ctypes.c_int
-        L.moe_expert_ffn.argtypes = [vp, vp, i32, shp, vp, vp, vp, vp, vp, u32, vp]
+        L.moe_expert_ffn.argtypes = [vp, vp, i32, shp, vp, vp, vp, vp, vp, vp, sz, u32, vp]
         L.moe_expert_ffn.restype = ctypes.c_int
         L.moe_combine.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, u32, vp]
         L.moe_combine.restype = ctypes.c_int
         L.moe_workspace_bytes.argtypes = [i32, i32, shp]
         L.moe_workspace_bytes.restype = sz
+        L.moe_ffn_workspace_bytes.argtypes = [i32, shp]
+        L.moe_ffn_workspace_bytes.restype = sz
         L.moe_status_string.argtypes = [ctypes.c_int]
         L.moe_status_string.restype = ctypes.c_char_p
         _lib = L
@@ -116,11 +118,16 @@ def moe_permute(x, topk_idx, T, k, shard: MoeShard, x_perm, expert_offsets, row_
                                             workspace_bytes, _stream(stream)))
 
 
+def moe_ffn_workspace_bytes(cap_rows, shard: MoeShard) -> int:
+    return int(lib().moe_ffn_workspace_bytes(cap_rows, ctypes.byref(shard)))
+
+
 def moe_expert_ffn(x_perm, expert_offsets, cap_rows, shard: MoeShard, w_gate, w_up, w_down, h_workspace, y_perm,
-                   flags=0, stream=None):
+                   workspace=None, flags=0, stream=None):
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check("moe_expert_ffn", lib().moe_expert_ffn(_ptr(x_perm), _ptr(expert_offsets), cap_rows, ctypes.byref(shard),
                                                   _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(h_workspace),
-                                                  _ptr(y_perm), flags, _stream(stream)))
+                                                  _ptr(y_perm), _ptr(workspace), wbytes, flags, _stream(stream)))
 
 
 def moe_combine(y_perm, slot_row, topk_w, T, k, H, y_shared, x, w_shared_gate, y_out, flags=0, stream=None):

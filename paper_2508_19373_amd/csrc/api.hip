@@ -42,6 +42,11 @@ size_t moe_workspace_bytes(int32_t T, int32_t k, const moe_shard_t* shard) {
   return 256;  // reserved: the single-workgroup index kernel keeps its counters in LDS
 }
 
+size_t moe_ffn_workspace_bytes(int32_t cap_rows, const moe_shard_t* shard) {
+  if (cap_rows < 0 || shard_status(shard) != MOE_OK) return 0;
+  return moe::ffn_workspace_bytes(cap_rows, shard->n_local_experts, shard->hidden, shard->inter_slice);
+}
+
 int moe_permute(const void* x_bf16, const int32_t* topk_idx, int32_t T, int32_t k, const moe_shard_t* shard,
                 void* x_perm, int32_t* expert_offsets, int32_t* row_src, int32_t* slot_row, void* workspace,
                 size_t workspace_bytes, void* stream) {
@@ -62,7 +67,7 @@ int moe_permute(const void* x_bf16, const int32_t* topk_idx, int32_t T, int32_t 
 
 int moe_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int32_t cap_rows, const moe_shard_t* shard,
                    const void* w_gate, const void* w_up, const void* w_down, void* h_workspace, void* y_perm,
-                   uint32_t flags, void* stream) {
+                   void* workspace, size_t workspace_bytes, uint32_t flags, void* stream) {
   const int st = shard_status(shard);
   if (st != MOE_OK) return st;
   if (cap_rows < 0 || (flags & ~(uint32_t)(MOE_Y_PERM_BF16 | MOE_FFN_SKIP_GATEUP | MOE_FFN_SKIP_DOWN)))
@@ -74,9 +79,11 @@ int moe_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int32_t ca
   if (!aligned16(x_perm) || !aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down) ||
       !aligned16(h_workspace) || !aligned16(y_perm))
     return MOE_ERR_INVALID_ARG;
+  const size_t need = moe_ffn_workspace_bytes(cap_rows, shard);
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned16(workspace))) return MOE_ERR_WORKSPACE;
   return hip_status(moe::launch_expert_ffn(x_perm, expert_offsets, cap_rows, shard->n_local_experts, shard->hidden,
-                                           shard->inter_slice, w_gate, w_up, w_down, h_workspace, y_perm,
-                                           flags, static_cast<hipStream_t>(stream)));
+                                           shard->inter_slice, w_gate, w_up, w_down, h_workspace, y_perm, workspace,
+                                           workspace_bytes, flags, static_cast<hipStream_t>(stream)));
 }
 
 int moe_combine(const void* y_perm, const int32_t* slot_row, const float* topk_w, int32_t T, int32_t k, int32_t H,

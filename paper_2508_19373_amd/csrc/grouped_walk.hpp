@@ -1,0 +1,193 @@
+// Grouped "NT" GEMM for decode-sized groups, register-resident activations (gfx950).
+//
+// Decode is bound by reading every active expert's weights from HBM once (paper, "Generative
+// Inference": the decoding stage is memory-bound by weight loading).  Measured on MI355X, a
+// kernel that re-reads the activation rows for every weight strip loses 10-40 % of the HBM
+// rate to the extra L1 requests, so here the activations never leave the register file:
+//  * a workgroup owns (expert, contiguous range of 16-feature strips, K slice); wavefront w
+//    owns k32 steps [w*STEPS, (w+1)*STEPS) of that slice and loads its MFMA A operands (the up
+//    to 16*MT activation rows, padded by clamping) ONCE, before walking the strips;
+//  * the weights then flow as one continuous stream of 1 KB loads (16 rows x 64 contiguous
+//    bytes, the pattern that measured best: ~6.4 TB/s) through a register ring RING loads deep,
+//    crossing strip boundaries without draining;
+//  * v_mfma_f32_16x16x32_bf16; per strip the NW partial tiles meet in a double-buffered LDS
+//    area (one barrier per strip) and are summed in wave order, so the result is deterministic;
+//  * K slices (grid.z > 1, down projection only) write fp32 partial outputs that a small
+//    second kernel adds in slice order;
+//  * experts without rows exit before touching their weights.
+#pragma once
+#include <type_traits>
+
+#include "moe_internal.hpp"
+
+namespace moe {
+namespace gw {
+
+__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.f + __expf(-g)) * u; }
+
+template <int LO, int HI, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (LO < HI) {
+    f(std::integral_constant<int, LO>{});
+    static_for<LO + 1, HI>(f);
+  }
+}
+
+// largest divisor of n in [6, 12], else the largest one below 6
+constexpr int ring_size(int n) {
+  for (int r = 12; r >= 6; --r)
+    if (n % r == 0) return r;
+  for (int r = 5; r >= 1; --r)
+    if (n % r == 0) return r;
+  return 1;
+}
+
+// MT = 1 is compiled for 4 wavefronts per SIMD (at most 128 VGPRs: two 8-wave workgroups per CU),
+// MT = 2 for 2 per SIMD.
+// grid = (strip ranges, n_local, K slices).  GATEUP: Wa = gate, Wb = up, C = h (bf16).
+// Else Wa = down and C = y (fp32) or, with K slices, the partial buffer [slice][cap_rows][n_out].
+template <int NW, int STEPS, int MT, bool GATEUP>
+__global__ __launch_bounds__(NW * 64, (MT == 1 ? 4 : 2)) void grouped_walk_kernel(
+    const uint16_t* __restrict__ A, const int32_t* __restrict__ expert_offsets, const uint16_t* __restrict__ Wa,
+    const uint16_t* __restrict__ Wb, int n_out, int K, void* __restrict__ Cv, int strips_per_wg, int cap_rows) {
+  constexpr int NB = GATEUP ? 2 : 1;
+  constexpr int ITEMS = NB * STEPS;  // weight loads (1 KB each) per strip per wave
+  constexpr int RING = ring_size(ITEMS);
+  constexpr int TILES = NB * MT;
+  __shared__ float red[2][NW][TILES][256];
+
+  const int e = blockIdx.y;
+  const int lo = expert_offsets[e], hi = expert_offsets[e + 1];
+  if (hi <= lo) return;  // inactive expert: its weights are never read
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15, kq = lane >> 4;
+  const int total_strips = n_out / 16;
+  const int s_begin = blockIdx.x * strips_per_wg;
+  const int s_end = min(s_begin + strips_per_wg, total_strips);
+  if (s_begin >= s_end) return;
+  const int n_strips = s_end - s_begin;
+  const int kbase = (blockIdx.z * NW + wave) * (STEPS * 32) + kq * 8;
+
+  const size_t eoff = (size_t)e * n_out * K;
+  const uint16_t* w_lane[NB];
+  w_lane[0] = Wa + eoff + (size_t)(s_begin * 16 + l16) * K + kbase;
+  if constexpr (GATEUP) w_lane[1] = Wb + eoff + (size_t)(s_begin * 16 + l16) * K + kbase;
+  const size_t strip_stride = (size_t)16 * K;
+
+  for (int m0 = lo; m0 < hi; m0 += 16 * MT) {
+    const int m_hi = min(m0 + 16 * MT, hi);
+    // ---- activations: loaded once, kept for every strip
+    bf16x8 a[STEPS][MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+      const uint16_t* ap = A + (size_t)min(m0 + t * 16 + l16, m_hi - 1) * K + kbase;
+#pragma unroll
+      for (int s = 0; s < STEPS; ++s) a[s][t] = *reinterpret_cast<const bf16x8*>(ap + s * 32);
+    }
+
+    // ---- weight stream: item j of strip si is matrix j / STEPS, k32 step j % STEPS
+    bf16x8 ring[RING];
+    auto load_item = [&](int si, auto j_tag, auto slot_tag) {
+      constexpr int j = decltype(j_tag)::value, slot = decltype(slot_tag)::value;
+      const int sc = min(si, n_strips - 1);  // past the range: re-read the last strip (unused)
+      ring[slot] = *reinterpret_cast<const bf16x8*>(w_lane[j / STEPS] + sc * strip_stride + (j % STEPS) * 32);
+    };
+    static_for<0, RING>([&](auto j_tag) { load_item(0, j_tag, j_tag); });
+
+    for (int si = 0; si < n_strips; ++si) {
+      f32x4 acc[NB][MT];
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) acc[b][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+      static_for<0, ITEMS>([&](auto j_tag) {
+        constexpr int j = decltype(j_tag)::value;
+        constexpr int slot = j % RING, b = j / STEPS, s = j % STEPS;
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+          acc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[s][t], ring[slot], acc[b][t], 0, 0, 0);
+        // refill the slot with the item RING ahead in the stream (next strip past the end)
+        constexpr int jn = (j + RING) % ITEMS;
+        load_item(si + ((j + RING) >= ITEMS ? 1 : 0), std::integral_constant<int, jn>{},
+                  std::integral_constant<int, slot>{});
+      });
+
+      // ---- partial tiles -> LDS (buffer si & 1), one barrier, fixed-order sum, epilogue
+      const int buf = si & 1;
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) red[buf][wave][b * MT + t][(kq * 4 + i) * 16 + l16] = acc[b][t][i];
+      __syncthreads();
+      const int col = (s_begin + si) * 16;
+      for (int idx = tid; idx < MT * 256; idx += NW * 64) {
+        const int t = idx >> 8, r = (idx >> 4) & 15, c = idx & 15;
+        const int row = m0 + t * 16 + r;
+        float sum[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          float v = 0.f;
+#pragma unroll
+          for (int w = 0; w < NW; ++w) v += red[buf][w][b * MT + t][r * 16 + c];
+          sum[b] = v;
+        }
+        if (row < m_hi) {
+          if constexpr (GATEUP) {
+            static_cast<uint16_t*>(Cv)[(size_t)row * n_out + col + c] =
+                (uint16_t)f32_to_bf16_bits(silu_mul(sum[0], sum[1]));
+          } else {
+            static_cast<float*>(Cv)[((size_t)blockIdx.z * cap_rows + row) * n_out + col + c] = sum[0];
+          }
+        }
+      }
+      // no second barrier: buffer `buf` is written again two strips later, after the next barrier
+    }
+    __syncthreads();  // before the next row pass reuses the LDS buffers
+  }
+}
+
+// y[r, n] = sum over K slices, in slice order, of partial[slice][r, n] for the rows in use.
+__global__ __launch_bounds__(256) void sum_slices_kernel(const float* __restrict__ partial,
+                                                        const int32_t* __restrict__ expert_offsets, int n_local,
+                                                        int cap_rows, int n_out, int n_slices, float* __restrict__ y) {
+  const int R = expert_offsets[n_local];
+  const size_t total = (size_t)R * n_out / 4;
+  const size_t slice_stride = (size_t)cap_rows * n_out / 4;
+  const float4* p = reinterpret_cast<const float4*>(partial);
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    float4 s = p[i];
+    for (int z = 1; z < n_slices; ++z) {
+      const float4 v = p[z * slice_stride + i];
+      s.x += v.x;
+      s.y += v.y;
+      s.z += v.z;
+      s.w += v.w;
+    }
+    reinterpret_cast<float4*>(y)[i] = s;
+  }
+}
+
+// How K is cut for the walk kernel: NW wavefronts x STEPS k32 steps per wavefront x slices.
+struct WalkPlan {
+  int nw, steps, slices;  // nw == 0: shape not covered, use the generic streaming kernel
+};
+inline WalkPlan plan_for(int K) {
+  const int steps32 = K / 32;
+  if (K % 32 == 0) {
+    const int nws[2] = {8, 4};
+    const int cand[5] = {16, 14, 11, 8, 7};
+    for (int nw : nws)
+      for (int st : cand) {
+        if (nw == 4 && !(st == 11 || st == 8)) continue;  // instantiated: (8,16) (8,14) (8,11) (8,8) (8,7) (4,11) (4,8)
+        if (steps32 % (nw * st) == 0) return WalkPlan{nw, st, steps32 / (nw * st)};
+      }
+  }
+  return WalkPlan{0, 0, 0};
+}
+
+}  // namespace gw
+}  // namespace moe

@@ -58,11 +58,14 @@ class ExpertShardLayer:
         self.h_ws = torch.empty((cap, self.shard.inter_slice), dtype=torch.bfloat16, device=d)
         self.y_perm = torch.empty((cap, H), dtype=ydt, device=d)
         self.workspace = torch.empty(max(B.moe_workspace_bytes(T, k, self.shard), 256), dtype=torch.uint8, device=d)
+        self.ffn_ws = torch.empty(max(B.moe_ffn_workspace_bytes(cap, self.shard), 256), dtype=torch.uint8, device=d)
         self.y_out = torch.empty((Tn, H), dtype=torch.float32 if self.out_f32 else torch.bfloat16, device=d)
         if self.shared is not None:
             self.sh_offsets = torch.zeros(2, dtype=torch.int32, device=d)
             self.h_sh = torch.empty((Tn, self.shared_shard.inter_slice), dtype=torch.bfloat16, device=d)
             self.y_shared = torch.empty((Tn, H), dtype=ydt, device=d)
+            self.ffn_ws_sh = torch.empty(max(B.moe_ffn_workspace_bytes(Tn, self.shared_shard), 256),
+                                         dtype=torch.uint8, device=d)
         self.Tmax = T
 
     def forward(self, x: torch.Tensor, logits: torch.Tensor | None = None, stream=None) -> torch.Tensor:
@@ -79,14 +82,14 @@ class ExpertShardLayer:
                       self.slot_row, self.workspace, stream=stream)
         yflag = B.MOE_Y_PERM_BF16 if self.y_perm_bf16 else 0
         B.moe_expert_ffn(self.x_perm, self.expert_offsets, T * k, self.shard, self.w_gate, self.w_up, self.w_down,
-                         self.h_ws, self.y_perm, yflag, stream)
+                         self.h_ws, self.y_perm, self.ffn_ws, yflag, stream)
         y_shared = None
         if self.shared is not None:
             if getattr(self, "_sh_T", None) != T:
                 self.sh_offsets.copy_(torch.tensor([0, T], dtype=torch.int32))
                 self._sh_T = T
             B.moe_expert_ffn(x, self.sh_offsets, T, self.shared_shard, self.shared[0], self.shared[1], self.shared[2],
-                             self.h_sh, self.y_shared, yflag, stream)
+                             self.h_sh, self.y_shared, self.ffn_ws_sh, yflag, stream)
             y_shared = self.y_shared
         cflags = yflag | (B.MOE_OUT_F32 if self.out_f32 else 0)
         gate_x = x if self.w_shared_gate is not None else None

@@ -82,7 +82,7 @@ def test_shard_descriptor_validation(lib, bad):
     s = _shard(**bad)
     assert B.moe_workspace_bytes(4, 2, s) == 0
     assert lib.moe_permute(P, P, 4, 2, ctypes.byref(s), P, P, P, P, P, 1024, None) == B.MOE_ERR_INVALID_ARG
-    assert lib.moe_expert_ffn(P, P, 8, ctypes.byref(s), P, P, P, P, P, 0, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_expert_ffn(P, P, 8, ctypes.byref(s), P, P, P, P, P, P, 1 << 30, 0, None) == B.MOE_ERR_INVALID_ARG
 
 
 def test_permute_validation(lib):
@@ -103,13 +103,21 @@ def test_permute_validation(lib):
 def test_expert_ffn_validation(lib):
     f = lib.moe_expert_ffn
     s = _shard()
-    assert f(P, P, -1, ctypes.byref(s), P, P, P, P, P, 0, None) == B.MOE_ERR_INVALID_ARG
-    assert f(P, P, 8, ctypes.byref(s), P, None, P, P, P, 0, None) == B.MOE_ERR_INVALID_ARG
-    assert f(P, P, 8, ctypes.byref(s), P, P, P, P, P, B.MOE_OUT_F32, None) == B.MOE_ERR_INVALID_ARG
-    assert f(P, P, 8, ctypes.byref(_shard(hidden=520)), P, P, P, P, P, 0, None) == B.MOE_ERR_UNSUPPORTED_SHAPE
-    assert f(P, P, 8, ctypes.byref(_shard(inter_full=1000, inter_slice=500)), P, P, P, P, P, 0, None) \
+    W = 1 << 30
+    assert f(P, P, -1, ctypes.byref(s), P, P, P, P, P, P, W, 0, None) == B.MOE_ERR_INVALID_ARG
+    assert f(P, P, 8, ctypes.byref(s), P, None, P, P, P, P, W, 0, None) == B.MOE_ERR_INVALID_ARG
+    assert f(P, P, 8, ctypes.byref(s), P, P, P, P, P, P, W, B.MOE_OUT_F32, None) == B.MOE_ERR_INVALID_ARG
+    assert f(P, P, 8, ctypes.byref(_shard(hidden=520)), P, P, P, P, P, P, W, 0, None) == B.MOE_ERR_UNSUPPORTED_SHAPE
+    assert f(P, P, 8, ctypes.byref(_shard(inter_full=1000, inter_slice=500)), P, P, P, P, P, P, W, 0, None) \
         == B.MOE_ERR_UNSUPPORTED_SHAPE
-    assert f(P, P, 8, ctypes.byref(s), P, P, P + 8, P, P, 0, None) == B.MOE_ERR_INVALID_ARG
+    assert f(P, P, 8, ctypes.byref(s), P, P, P + 8, P, P, P, W, 0, None) == B.MOE_ERR_INVALID_ARG
+    # decode-sized call on a Mixtral-shaped shard needs split-K scratch; a prefill-sized one does not
+    mix = _shard(hidden=4096, inter_full=14336, inter_slice=14336)
+    need = B.moe_ffn_workspace_bytes(32, mix)
+    assert need == 4 * 32 * 4096 * 4
+    assert B.moe_ffn_workspace_bytes(8192, mix) == 0
+    assert f(P, P, 32, ctypes.byref(mix), P, P, P, P, P, None, 0, 0, None) == B.MOE_ERR_WORKSPACE
+    assert f(P, P, 32, ctypes.byref(mix), P, P, P, P, P, P, need - 1, 0, None) == B.MOE_ERR_WORKSPACE
 
 
 def test_combine_validation(lib):

@@ -141,8 +141,9 @@ def _ffn_gpu(x_perm_bits, offs, shard, wg, wu, wd, y_bf16=False):
     h_ws = torch.empty((cap, shard.inter_slice), dtype=torch.bfloat16, device="cuda")
     y = torch.full((cap, shard.hidden), float("nan"), dtype=torch.bfloat16 if y_bf16 else torch.float32,
                    device="cuda")
+    ws = torch.empty(max(B.moe_ffn_workspace_bytes(cap, shard), 16), dtype=torch.uint8, device="cuda")
     B.moe_expert_ffn(bf16_tensor(x_perm_bits), _dev(offs), cap, shard, bf16_tensor(wg), bf16_tensor(wu),
-                     bf16_tensor(wd), h_ws, y, B.MOE_Y_PERM_BF16 if y_bf16 else 0)
+                     bf16_tensor(wd), h_ws, y, ws, B.MOE_Y_PERM_BF16 if y_bf16 else 0)
     torch.cuda.synchronize()
     return y.float().cpu().numpy().astype(np.float64)
 
@@ -155,6 +156,12 @@ def _ffn_gpu(x_perm_bits, offs, shard, wg, wu, wd, y_bf16=False):
     (2048, 704, [3, 0, 9, 1]),
     (320, 448, [700, 0, 300, 257, 1]),               # large groups: the 256x256 LDS-DMA kernel, ragged everywhere
     (512, 1024, [256, 512]),                         # exact multiples of the tile
+    (4096, 3584, [2, 0, 5, 1]),                      # decode: register-resident activations, 8x16 / 8x14 splits
+    (4096, 14336, [3, 1]),                           # decode: down projection in 4 K slices + slice sum
+    (2048, 1408, [1, 0, 4, 0, 2, 16]),               # decode: 8x8 and 4x11 splits
+    (2048, 5632, [12]),                              # shared-expert shape at decode, 2 K slices
+    (512, 1024, [16, 2, 0, 9]),                      # decode: generic streaming (H) + 4x8 split (I)
+    (512, 1024, [40, 30, 7]),                        # decode regime with more than 32 rows in one expert
 ])
 def test_expert_ffn_against_oracle(H, I_s, counts):
     n = len(counts)
