@@ -77,6 +77,8 @@ def main():
     ap.add_argument("--workload", default="mixtral_prefill", choices=sorted(WORKLOADS))
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", choices=["auto", "on", "off"], default="auto",
+                    help="replay the layer as one HIP graph (auto: when an eager step takes < 1 ms)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens the oracle is timed on (0 = auto)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -105,14 +107,21 @@ def main():
     def step():
         return layer.forward(x, logits)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    eager_ms = timed(step)
+    ms_per_step, mode = eager_ms, "eager"
+    if args.graph == "on" or (args.graph == "auto" and eager_ms < 1.0):
+        graph, _ = layer.capture(x, logits)
+        ms_per_step, mode = timed(graph.replay), "hip-graph"
 
     counts = np.diff(layer.expert_offsets.cpu().numpy())
     flops, min_bytes, R, active = algorithmic_work(shape, T, counts)
@@ -197,7 +206,7 @@ def main():
                    "n_local_experts": shape.n_local_experts, "expert_offset": shape.expert_offset, "seed": args.seed},
         "pct_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS, "min_bytes_gbs": gbs,
         "pct_hbm_peak": 100.0 * gbs / PEAK_HBM_GBS, "flops_per_layer": flops, "min_bytes_per_layer": min_bytes,
-        "breakdown_ms": br, "input_gen_s": gen_s, "roofline": roofline, "cpu_baseline": cpu,
+        "launch_mode": mode, "eager_ms_per_step": eager_ms, "breakdown_ms": br, "input_gen_s": gen_s, "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
 

@@ -120,18 +120,19 @@ __global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(
 
 // Router logits as a small fp32 MFMA GEMM: logits[16 tokens, 16 experts] tiles with
 // v_mfma_f32_16x16x4_f32 (x is widened bf16 -> fp32 exactly, W_r is read as it is laid out,
-// [H,E] row-major = the B operand's natural k-major form).  A workgroup owns 16 tokens; its 4
-// wavefronts split the hidden dimension in 32-wide chunks and the partial tiles are summed in a
-// fixed order through LDS.  The sum over k may be taken in any order, so one 16-byte load per
-// lane feeds 8 MFMAs: in MFMA s, lane (m, kq) supplies x[t0+m, c*32 + kq*8 + s] and the B lane
-// (n, kq) the matching W_r row.
+// [H,E] row-major = the B operand's natural k-major form).  A workgroup owns 16 tokens; its NWV
+// wavefronts split the hidden dimension in 32-wide chunks (UNR chunks' loads are issued before
+// their MFMAs, so a decode-sized call is a couple of memory round trips, not one per chunk) and
+// the partial tiles are summed in wave order through LDS.  The sum over k may be taken in any
+// order, so one 16-byte load per lane feeds 8 MFMAs: in MFMA s, lane (m, kq) supplies
+// x[t0+m, c*32 + kq*8 + s] and the B lane (n, kq) the matching W_r row.
 constexpr int kLogitTok = 16;
 
-template <int NT>  // 16-expert column tiles
-__global__ __launch_bounds__(256) void router_logits_kernel(const uint16_t* __restrict__ x,
-                                                            const float* __restrict__ w_router,
-                                                            float* __restrict__ logits, int T, int H, int E) {
-  __shared__ float part[4][NT][16][17];
+template <int NT, int NWV, int UNR>  // 16-expert column tiles, wavefronts, chunks in flight per wavefront
+__global__ __launch_bounds__(NWV * 64) void router_logits_kernel(const uint16_t* __restrict__ x,
+                                                                 const float* __restrict__ w_router,
+                                                                 float* __restrict__ logits, int T, int H, int E) {
+  __shared__ float part[NWV][NT][16][17];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int t0 = blockIdx.x * kLogitTok;
   const int m = lane & 15, kq = lane >> 4;
@@ -141,18 +142,28 @@ __global__ __launch_bounds__(256) void router_logits_kernel(const uint16_t* __re
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
   const int n_chunks = H / 32;
-  for (int c = wave; c < n_chunks; c += 4) {
-    const uint4 xv = *reinterpret_cast<const uint4*>(xr + c * 32);
-    const float xf[8] = {bf16_lo(xv.x), bf16_hi(xv.x), bf16_lo(xv.y), bf16_hi(xv.y),
-                         bf16_lo(xv.z), bf16_hi(xv.z), bf16_lo(xv.w), bf16_hi(xv.w)};
-    const float* wr = w_router + (size_t)(c * 32 + kq * 8) * E + m;
+  for (int c0 = wave; c0 < n_chunks; c0 += NWV * UNR) {
+    uint4 xv[UNR];
+    float wv[UNR][8][NT];
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
+    for (int u = 0; u < UNR; ++u) {
+      const int c = min(c0 + u * NWV, n_chunks - 1);  // past the end: re-read, weight forced to 0 below
+      const bool live = c0 + u * NWV < n_chunks;
+      xv[u] = *reinterpret_cast<const uint4*>(xr + c * 32);
+      const float* wr = w_router + (size_t)(c * 32 + kq * 8) * E + m;
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const float b = (nt * 16 + m < E) ? wr[(size_t)s * E + nt * 16] : 0.f;
-        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(xf[s], b, acc[nt], 0, 0, 0);
-      }
+      for (int s = 0; s < 8; ++s)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) wv[u][s][nt] = (live && nt * 16 + m < E) ? wr[(size_t)s * E + nt * 16] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const float xf[8] = {bf16_lo(xv[u].x), bf16_hi(xv[u].x), bf16_lo(xv[u].y), bf16_hi(xv[u].y),
+                           bf16_lo(xv[u].z), bf16_hi(xv[u].z), bf16_lo(xv[u].w), bf16_hi(xv[u].w)};
+#pragma unroll
+      for (int s = 0; s < 8; ++s)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(xf[s], wv[u][s][nt], acc[nt], 0, 0, 0);
     }
   }
 #pragma unroll
@@ -160,19 +171,22 @@ __global__ __launch_bounds__(256) void router_logits_kernel(const uint16_t* __re
 #pragma unroll
     for (int i = 0; i < 4; ++i) part[wave][nt][kq * 4 + i][m] = acc[nt][i];
   __syncthreads();
-  for (int idx = tid; idx < NT * 256; idx += 256) {
+  for (int idx = tid; idx < NT * 256; idx += NWV * 64) {
     const int nt = idx >> 8, row = (idx >> 4) & 15, col = idx & 15;
     const int e = nt * 16 + col, t = t0 + row;
-    if (e < E && t < T)
-      logits[(size_t)t * E + e] = ((part[0][nt][row][col] + part[1][nt][row][col]) + part[2][nt][row][col]) +
-                                  part[3][nt][row][col];
+    if (e < E && t < T) {
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < NWV; ++w) sum += part[w][nt][row][col];
+      logits[(size_t)t * E + e] = sum;
+    }
   }
 }
 
-template <int NT>
+template <int NT, int NWV, int UNR>
 void launch_logits(const uint16_t* x, const float* w_router, float* logits, int T, int H, int E, hipStream_t stream) {
-  hipLaunchKernelGGL(router_logits_kernel<NT>, dim3((T + kLogitTok - 1) / kLogitTok), dim3(256), 0, stream, x,
-                     w_router, logits, T, H, E);
+  hipLaunchKernelGGL((router_logits_kernel<NT, NWV, UNR>), dim3((T + kLogitTok - 1) / kLogitTok), dim3(NWV * 64), 0,
+                     stream, x, w_router, logits, T, H, E);
 }
 
 }  // namespace
@@ -185,11 +199,11 @@ hipError_t launch_route_topk(const void* x, const float* w_router, float* logits
   if (!(flags & MOE_LOGITS_GIVEN) && H % 32 == 0) {
     // logits by MFMA first, then the selection kernel reads them back as given logits
     const int nt = (E + 15) / 16;
-    if (nt <= 1) launch_logits<1>(xs, w_router, logits, T, H, E, stream);
-    else if (nt <= 2) launch_logits<2>(xs, w_router, logits, T, H, E, stream);
-    else if (nt <= 4) launch_logits<4>(xs, w_router, logits, T, H, E, stream);
-    else if (nt <= 8) launch_logits<8>(xs, w_router, logits, T, H, E, stream);
-    else launch_logits<16>(xs, w_router, logits, T, H, E, stream);
+    if (nt <= 1) launch_logits<1, 16, 4>(xs, w_router, logits, T, H, E, stream);
+    else if (nt <= 2) launch_logits<2, 16, 4>(xs, w_router, logits, T, H, E, stream);
+    else if (nt <= 4) launch_logits<4, 16, 2>(xs, w_router, logits, T, H, E, stream);
+    else if (nt <= 8) launch_logits<8, 8, 1>(xs, w_router, logits, T, H, E, stream);
+    else launch_logits<16, 4, 1>(xs, w_router, logits, T, H, E, stream);
     const hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     flags |= MOE_LOGITS_GIVEN;

@@ -86,6 +86,8 @@ class ExpertShardLayer:
         y_shared = None
         if self.shared is not None:
             if getattr(self, "_sh_T", None) != T:
+                if torch.cuda.is_current_stream_capturing():
+                    raise RuntimeError("run one eager forward with this token count before capturing a graph")
                 self.sh_offsets.copy_(torch.tensor([0, T], dtype=torch.int32))
                 self._sh_T = T
             B.moe_expert_ffn(x, self.sh_offsets, T, self.shared_shard, self.shared[0], self.shared[1], self.shared[2],
@@ -96,6 +98,22 @@ class ExpertShardLayer:
         B.moe_combine(self.y_perm, self.slot_row, self.topk_w, T, k, H, y_shared, gate_x, self.w_shared_gate,
                       self.y_out, cflags, stream)
         return self.y_out[:T]
+
+    def capture(self, x: torch.Tensor, logits: torch.Tensor | None = None):
+        """Capture one forward on (x, logits) into a HIP graph; returns (graph, output view).
+        Decode-sized layers are a chain of short kernels, so replaying a graph removes most of
+        the launch gaps.  The library enqueues kernels only (no memset nodes, no allocation),
+        which is what makes the capture legal; x / logits are read in place at every replay."""
+        self.forward(x, logits)  # eager warm-up: sizes the buffers, sets the shared-expert offsets
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                out = self.forward(x, logits)
+        torch.cuda.current_stream().wait_stream(side)
+        return graph, out
 
     @classmethod
     def from_inputs(cls, li, **kw) -> "ExpertShardLayer":

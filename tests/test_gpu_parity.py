@@ -337,3 +337,27 @@ def test_layer_is_deterministic_and_buffers_reusable():
     assert np.array_equal(li_small.x, li.x[:37])
     ref = _oracle_layer(li_small, layer.logits[:37].cpu().numpy())  # same rows, same logits as the full batch
     assert _rel(y_small.float().cpu().numpy().astype(np.float64), ref) < REL_L2
+
+
+def test_graph_replay_matches_eager():
+    """A captured layer must give the eager result on every replay, with eager work and
+    synchronisations in between (the library records kernels only, never memset nodes)."""
+    li = I.make_layer_inputs(SMALL_QWEN, 32, 0)
+    layer = ExpertShardLayer.from_inputs(li)
+    x = bf16_tensor(li.x)
+    eager = layer.forward(x).clone()
+    graph, out = layer.capture(x)
+    for i in range(4):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), "replay %d differs from eager" % i
+        other = layer.forward(bf16_tensor(I.make_x(i + 1, 32, SMALL_QWEN.hidden))).clone()  # eager work in between
+        torch.cuda.synchronize()
+        assert not torch.equal(other, eager)
+    # new contents in the same input buffer are picked up by the next replay
+    x2 = bf16_tensor(I.make_x(9, 32, SMALL_QWEN.hidden))
+    want = layer.forward(x2).clone()
+    x.copy_(x2)
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out, want)
