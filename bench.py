@@ -25,6 +25,14 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 
+# HBM-side bytes per launch of the dominant kernel (GEMM1 + SwiGLU), from two rocprofv3 --pmc runs
+# (FETCH_SIZE, WRITE_SIZE in KiB per dispatch; see profiles/<workload>_rocprofv3.txt), each scaled by
+# what the same counter reads for a plain 1 GiB device copy: FETCH_SIZE x 2.0, WRITE_SIZE x 1.0.
+MEASURED_TRAFFIC_BYTES = {
+    "mixtral_prefill": (3532900.3 * 2.0 + 245983.7) * 1024,
+    "mixtral_decode": (949376.6 * 2.0 + 11141.5) * 1024,
+}
+
 # name -> (inputs.WORKLOADS key, token count, description)
 WORKLOADS = {
     "tiny": ("tiny", 64, "tiny 512/8e/top2/1024 T=64"),
@@ -77,6 +85,8 @@ def main():
     ap.add_argument("--workload", default="mixtral_prefill", choices=sorted(WORKLOADS))
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain 1 GiB device copies, to scale FETCH_SIZE / WRITE_SIZE counters under rocprofv3")
     ap.add_argument("--graph", choices=["auto", "on", "off"], default="auto",
                     help="replay the layer as one HIP graph (auto: when an eager step takes < 1 ms)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens the oracle is timed on (0 = auto)")
@@ -94,6 +104,14 @@ def main():
         sys.exit("bench.py needs a GPU")
     B.lib()  # fail loudly when the HIP library is missing
     torch.cuda.set_device(0)
+
+    if args.copy_calibration:  # a kernel of known traffic: reads 1 GiB, writes 1 GiB per launch
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     key, T, desc = WORKLOADS[args.workload]
     shape, _ = I.WORKLOADS[key]
@@ -158,22 +176,27 @@ def main():
     g1_flops = 4.0 * R * H * I_s
     g1_bytes = 2.0 * active * H * I_s * 2 + R * H * 2 + R * I_s * 2
     intensity = g1_flops / g1_bytes
+    decode = (T * k) // shape.n_local_experts <= 40
+    kname = ("moe::gw::grouped_walk_kernel<..., GATEUP> (GEMM1 + SwiGLU, weight streaming)" if decode
+             else "moe::gg::grouped_gemm_dlds_kernel<256, GATEUP> (GEMM1 + SwiGLU)")
     if intensity > PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
         ach = g1_flops / (g1_ms * 1e-3) / 1e12
-        roofline = {"kernel": "grouped_gemm_kernel<GATEUP> (GEMM1 + SwiGLU)", "bound": "mfma", "achieved": ach,
-                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
-                    "ms": g1_ms, "flops_per_launch": g1_flops}
+        roofline = {"kernel": kname, "bound": "mfma", "achieved": ach,
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                    "ms": g1_ms, "flops_per_launch": g1_flops, "algorithmic_bytes_per_launch": g1_bytes}
     else:
         ach = g1_bytes / (g1_ms * 1e-3) / 1e9
-        roofline = {"kernel": "grouped_gemm_kernel<GATEUP> (GEMM1 + SwiGLU)", "bound": "hbm", "achieved": ach,
-                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None,
+        roofline = {"kernel": kname, "bound": "hbm", "achieved": ach,
+                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
                     "ms": g1_ms, "bytes_per_launch": g1_bytes}
 
     # ---- CPU baseline: the oracle as it stands on a bounded token sample
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import moe_oracle as O
-        n = args.cpu_sample_tokens or min(T, 32)
+        n = args.cpu_sample_tokens or min(T, 512)
         sel = np.linspace(0, T - 1, n).astype(np.int64)
         lg = layer.logits[:T].cpu().numpy()[sel]
         shared = (li.ws_gate, li.ws_up, li.ws_down) if li.ws_gate is not None else None
