@@ -39,7 +39,7 @@ int moe_route_topk(const void* x_bf16, const float* w_router, float* logits, int
 
 size_t moe_workspace_bytes(int32_t T, int32_t k, const moe_shard_t* shard) {
   if (T < 0 || k < 1 || k > MOE_MAX_TOPK || shard_status(shard) != MOE_OK) return 0;
-  return 256;  // reserved: the single-workgroup index kernel keeps its counters in LDS
+  return moe::permute_workspace_bytes(T, k, shard->n_local_experts);
 }
 
 size_t moe_ffn_workspace_bytes(int32_t cap_rows, const moe_shard_t* shard) {
@@ -61,7 +61,7 @@ int moe_permute(const void* x_bf16, const int32_t* topk_idx, int32_t T, int32_t 
   if (!aligned16(x_bf16) || !aligned16(x_perm)) return MOE_ERR_INVALID_ARG;
   if (workspace == nullptr || workspace_bytes < moe_workspace_bytes(T, k, shard)) return MOE_ERR_WORKSPACE;
   return hip_status(moe::launch_permute(x_bf16, topk_idx, T, k, shard->hidden, shard->n_local_experts,
-                                        shard->expert_offset, x_perm, expert_offsets, row_src, slot_row,
+                                        shard->expert_offset, x_perm, expert_offsets, row_src, slot_row, workspace,
                                         static_cast<hipStream_t>(stream)));
 }
 

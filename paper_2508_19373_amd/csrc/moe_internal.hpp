@@ -40,7 +40,8 @@ hipError_t launch_route_topk(const void* x, const float* w_router, float* logits
                              uint32_t flags, int32_t* topk_idx, float* topk_w, hipStream_t stream);
 hipError_t launch_permute(const void* x, const int32_t* topk_idx, int T, int k, int H, int n_local, int offset,
                           void* x_perm, int32_t* expert_offsets, int32_t* row_src, int32_t* slot_row,
-                          hipStream_t stream);
+                          void* workspace, hipStream_t stream);
+size_t permute_workspace_bytes(int T, int k, int n_local);
 hipError_t launch_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int cap_rows, int n_local, int H,
                              int I_s, const void* w_gate, const void* w_up, const void* w_down, void* h_ws,
                              void* y_perm, void* workspace, size_t workspace_bytes, uint32_t flags, hipStream_t stream);

@@ -2,7 +2,7 @@
 // Architectures"), restricted to the contiguous expert subset an expert-parallel shard holds
 // ("Expert Parallelism").  A stable counting sort of assignment ids a = t*k + j by expert id.
 //
-// Index kernel: one 1024-thread workgroup.  Pass 1 builds the per-expert histogram with LDS
+// Index kernel for small batches: one 1024-thread workgroup.  Pass 1 builds the per-expert histogram with LDS
 // integer atomics (order-independent result) and scans it.  Pass 2 walks the assignments in
 // order, 1024 at a time: inside a wavefront the rank among equal experts comes from ballot +
 // popcount, across the 16 wavefronts from a short serial prefix in LDS -- no order-dependent
@@ -97,6 +97,94 @@ __global__ __launch_bounds__(kIdxThreads) void permute_index_kernel(const int32_
   }
 }
 
+// ---- large batches: the same stable order from three short kernels over many workgroups.
+// (1) every workgroup ranks its own 1024 assignments (ballot inside a wavefront, serial prefix
+// over its 16 wavefronts) and publishes its per-expert counts; (2) one workgroup turns the counts
+// into per-(workgroup, expert) base rows (scan over workgroups, then over experts); (3) every
+// workgroup adds its bases.  No atomics on the value path: the order is the unique stable one.
+__global__ __launch_bounds__(kIdxThreads) void permute_rank_kernel(const int32_t* __restrict__ topk_idx, int A,
+                                                                  int n_local, int offset,
+                                                                  int32_t* __restrict__ block_counts,
+                                                                  int32_t* __restrict__ slot_row) {
+  __shared__ int32_t wave_cnt[kIdxWaves][MOE_MAX_EXPERTS];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
+  for (int i = tid; i < kIdxWaves * n_local; i += kIdxThreads) wave_cnt[i / n_local][i % n_local] = 0;
+  __syncthreads();
+  const int a = blockIdx.x * kIdxThreads + tid;
+  int e = -1;
+  if (a < A) {
+    e = topk_idx[a] - offset;
+    if (e < 0 || e >= n_local) e = -1;
+  }
+  int rank = 0;
+  unsigned long long todo = __ballot(e >= 0);
+  while (todo) {
+    const int leader = __ffsll((long long)todo) - 1;
+    const int le = __shfl(e, leader, kWave);
+    const unsigned long long m = __ballot(e == le);
+    if (e == le) rank = __popcll(m & ((1ull << lane) - 1ull));
+    if (lane == leader) wave_cnt[wv][le] = __popcll(m);
+    todo &= ~m;
+  }
+  __syncthreads();
+  for (int ee = tid; ee < n_local; ee += kIdxThreads) {
+    int run = 0;
+#pragma unroll
+    for (int w = 0; w < kIdxWaves; ++w) {
+      const int c = wave_cnt[w][ee];
+      wave_cnt[w][ee] = run;
+      run += c;
+    }
+    block_counts[(size_t)blockIdx.x * n_local + ee] = run;
+  }
+  __syncthreads();
+  // hand-over to the place kernel through slot_row: rank inside the workgroup (< 1024) in the low
+  // 10 bits, local expert (< 256) above them
+  if (a < A) slot_row[a] = (e >= 0) ? ((e << 10) | (wave_cnt[wv][e] + rank)) : -1;
+}
+
+__global__ __launch_bounds__(256) void permute_scan_kernel(int32_t* __restrict__ block_counts, int n_blocks,
+                                                          int n_local, int32_t* __restrict__ expert_offsets) {
+  __shared__ int32_t total[MOE_MAX_EXPERTS];
+  const int tid = threadIdx.x;
+  for (int e = tid; e < n_local; e += 256) {
+    int run = 0;
+    for (int b = 0; b < n_blocks; ++b) {
+      const int c = block_counts[(size_t)b * n_local + e];
+      block_counts[(size_t)b * n_local + e] = run;
+      run += c;
+    }
+    total[e] = run;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    for (int e = 0; e < n_local; ++e) {
+      const int c = total[e];
+      total[e] = run;
+      expert_offsets[e] = run;
+      run += c;
+    }
+    expert_offsets[n_local] = run;
+  }
+  __syncthreads();
+  for (int i = tid; i < n_blocks * n_local; i += 256) block_counts[i] += total[i % n_local];
+}
+
+__global__ __launch_bounds__(kIdxThreads) void permute_place_kernel(int A, int n_local,
+                                                                   const int32_t* __restrict__ block_bases,
+                                                                   int32_t* __restrict__ row_src,
+                                                                   int32_t* __restrict__ slot_row) {
+  const int a = blockIdx.x * kIdxThreads + threadIdx.x;
+  if (a >= A) return;
+  const int v = slot_row[a];
+  if (v < 0) return;
+  const int e = v >> 10, rank = v & 1023;
+  const int row = block_bases[(size_t)blockIdx.x * n_local + e] + rank;
+  slot_row[a] = row;
+  row_src[row] = a;
+}
+
 constexpr int kGatherThreads = 256;
 
 __global__ __launch_bounds__(kGatherThreads) void gather_rows_kernel(const uint4* __restrict__ x,
@@ -115,13 +203,30 @@ __global__ __launch_bounds__(kGatherThreads) void gather_rows_kernel(const uint4
 
 }  // namespace
 
+size_t permute_workspace_bytes(int T, int k, int n_local) {
+  const size_t blocks = ((size_t)T * k + kIdxThreads - 1) / kIdxThreads;
+  return 256 + blocks * n_local * sizeof(int32_t);
+}
+
 hipError_t launch_permute(const void* x, const int32_t* topk_idx, int T, int k, int H, int n_local, int offset,
                           void* x_perm, int32_t* expert_offsets, int32_t* row_src, int32_t* slot_row,
-                          hipStream_t stream) {
+                          void* workspace, hipStream_t stream) {
   const int A = T * k;
-  hipLaunchKernelGGL(permute_index_kernel, dim3(1), dim3(kIdxThreads), 0, stream, topk_idx, A, n_local, offset,
-                     expert_offsets, row_src, slot_row);
-  hipError_t err = hipGetLastError();
+  hipError_t err;
+  if (A <= 2 * kIdxThreads) {  // small batch: one workgroup does it all in one launch
+    hipLaunchKernelGGL(permute_index_kernel, dim3(1), dim3(kIdxThreads), 0, stream, topk_idx, A, n_local, offset,
+                       expert_offsets, row_src, slot_row);
+    err = hipGetLastError();
+  } else {
+    const int blocks = (A + kIdxThreads - 1) / kIdxThreads;
+    int32_t* counts = static_cast<int32_t*>(workspace);
+    hipLaunchKernelGGL(permute_rank_kernel, dim3(blocks), dim3(kIdxThreads), 0, stream, topk_idx, A, n_local, offset,
+                       counts, slot_row);
+    hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(256), 0, stream, counts, blocks, n_local, expert_offsets);
+    hipLaunchKernelGGL(permute_place_kernel, dim3(blocks), dim3(kIdxThreads), 0, stream, A, n_local, counts, row_src,
+                       slot_row);
+    err = hipGetLastError();
+  }
   if (err != hipSuccess || A == 0) return err;
   const int grid = A < 8192 ? A : 8192;
   hipLaunchKernelGGL(gather_rows_kernel, dim3(grid), dim3(kGatherThreads), 0, stream,

@@ -73,6 +73,14 @@ class ExpertShardLayer:
         if T > self.Tmax:
             self._alloc(T)
         k, H, E = self.k, self.H, self.E
+        # the FFN scratch depends on the regime (decode-sized calls need split-K partials)
+        need = B.moe_ffn_workspace_bytes(T * k, self.shard)
+        if need > self.ffn_ws.numel():
+            self.ffn_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+        if self.shared is not None:
+            need = B.moe_ffn_workspace_bytes(T, self.shared_shard)
+            if need > self.ffn_ws_sh.numel():
+                self.ffn_ws_sh = torch.empty(need, dtype=torch.uint8, device=self.device)
         flags = B.MOE_RENORM_TOPK if self.renorm else 0
         if logits is not None:
             self.logits[:T].copy_(logits)
