@@ -7,15 +7,17 @@
 // silu(g) * u sit in the same lane and the activation never leaves registers.
 //
 // Design for CDNA4:
-//  * one workgroup per (expert, row block, column block) tile; v_mfma_f32_32x32x16_bf16;
+//  * one workgroup per (expert, row block, column block) tile, 4 wavefronts of 128 x 128 outputs;
 //  * operands go global -> LDS directly (global_load_lds_dwordx4, no VGPR staging), two LDS
 //    stages of BM x 64 + BN x 64 bf16;
 //  * LDS rows are 128 bytes; the 16-byte chunk index is XOR-swizzled with (row/2)%8, applied
 //    on the global side of the DMA (a lane fetches the chunk that belongs at its LDS slot),
 //    so operand reads (ds_read_b128) are bank-conflict free;
-//  * one barrier per k-tile, placed after the last operand read of the tile, so the refill
-//    of the stage just consumed and the first operand reads of the next tile overlap with the
-//    last quarter of the tile's MFMAs;
+//  * v_mfma_f32_16x16x32_bf16 in back-to-back pairs on one accumulator, operands of the whole
+//    k-tile resident in registers and refreshed in place (see gemm_tile): the chip is power
+//    limited, and this instruction mix sustains the most FLOP/s at the cap;
+//  * one barrier per k-tile; DMA issue and operand reads are spread between the MFMA pairs in a
+//    fixed, fenced order (a burst of DMA instructions stalls the wave on the address unit);
 //  * tile ids are remapped so that each of the 8 XCDs (which get workgroups round-robin) works
 //    on a contiguous run of tiles that share A and B panels in its own L2.
 #pragma once
@@ -34,7 +36,6 @@ typedef __attribute__((address_space(1))) const void global_void_t;
 
 __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 __device__ __forceinline__ int lds_off(int row, int chunk) { return row * BK + ((chunk ^ swz(row)) << 3); }
-__device__ __forceinline__ int acc_row(int i, int lane) { return ((i >> 2) << 3) + ((lane >> 5) << 2) + (i & 3); }
 __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.f + __expf(-g)) * u; }
 
 // s_waitcnt with only vmcnt / only lgkmcnt constrained (gfx9 encoding)
@@ -124,28 +125,43 @@ __device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ exper
   return t;
 }
 
-// One (BM x BN) output tile, computed by the whole workgroup of WM x WN wavefronts.
+// One (BM x BN) output tile, computed by the whole workgroup of WM x WN wavefronts, on
+// v_mfma_f32_16x16x32_bf16 with the k-tile's operands resident in registers.
+//
+// MI355X is power-limited under dense MFMA load, and pairs of 16x16x32 MFMAs issued back to back
+// on the same accumulator sustain ~12 % more FLOP/s at the power cap than 32x32x16 (they move
+// half the accumulator bytes per FLOP).  Pairing needs both k32 halves of a 64-wide k-tile for
+// the same accumulator, so the operands of the WHOLE k-tile live in registers (2*(TM+TN)
+// fragments) and are refreshed in place: a fragment is re-read from the next k-tile's LDS stage
+// right after its last use.  LDS is then a two-stage landing buffer in front of the register
+// tile (a three-deep pipeline), still with one barrier per k-tile.
+// Order inside a k-tile: for row block i, for column block j: MFMA(k-half 0), MFMA(k-half 1).
+//   row 0        : refresh A[TM-1] from this tile's stage (its last use was the previous tile's end)
+//   barrier      : after row 0 -- every wave is done with the previous refreshes, tile kt+1 landed
+//   rows 1..TM-2 : DMA of tile kt+2 into the stage just freed, spread between the MFMA pairs
+//   row i >= 1   : refresh A[i-1] from tile kt+1's stage
+//   row TM-1     : refresh B[j] after its last use (i = TM-1)
 template <int BM, int BN, int WM, int WN, bool GATEUP, typename OutT>
 __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, const uint16_t* __restrict__ A,
-                                          int cap_rows, const uint16_t* __restrict__ B0,
-                                          const uint16_t* __restrict__ B1, int n_out, int K,
-                                          OutT* __restrict__ C) {
+                                            int cap_rows, const uint16_t* __restrict__ B0,
+                                            const uint16_t* __restrict__ B1, int n_out, int K,
+                                            OutT* __restrict__ C) {
   constexpr int NW = WM * WN;
-  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-  constexpr int A_INST = BM / 8 / NW, B_INST = BN / 8 / NW;  // DMA instructions per wave per k-tile
+  constexpr int TM = BM / WM / 16, TN = BN / WN / 16;
+  constexpr int A_INST = BM / 8 / NW, B_INST = BN / 8 / NW;
   constexpr int NCOLS = GATEUP ? BN / 2 : BN;
-  constexpr int STAGE = (BM + BN) * BK;  // uint16 elements per stage
-  static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "tile / wave grid mismatch");
+  constexpr int STAGE = (BM + BN) * BK;
+  constexpr int NP = TM * TN;  // MFMA pairs per k-tile
+  static_assert(BM % (WM * 16) == 0 && BN % (WN * 16) == 0, "tile / wave grid mismatch");
   static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "loader mismatch");
   static_assert(!GATEUP || (TN % 2 == 0), "gate and up column blocks must pair up inside a wave");
+  static_assert(TM >= 3, "needs a first, a middle and a last row block");
   const int row0 = tc.row0, hi = tc.row_end, col0 = tc.nb * NCOLS;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
 
-  // ---- DMA addressing: instruction `inst` fills LDS rows [8*inst, 8*inst+8); lane -> row
-  // 8*inst + lane/8, physical chunk lane%8, which must hold logical chunk (lane%8) ^ swz(row).
   const uint16_t* a_src[A_INST];
   const uint16_t* b_src[B_INST];
 #pragma unroll
@@ -153,7 +169,7 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
     const int inst = j * NW + wave;
     const int r = inst * 8 + (lane >> 3);
     const int c = (lane & 7) ^ swz(r);
-    const int gr = min(row0 + r, cap_rows - 1);  // rows past the group are fetched, never stored
+    const int gr = min(row0 + r, cap_rows - 1);
     a_src[j] = A + (size_t)gr * K + c * 8;
   }
   const size_t expert_stride = (size_t)n_out * K;
@@ -164,9 +180,9 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
     const int c = (lane & 7) ^ swz(r);
     const uint16_t* base = B0;
     int wrow;
-    if (GATEUP) {  // 32-row blocks alternate gate, up, gate, up ... of the same output columns
-      const int jb = r >> 5;
-      wrow = col0 + (jb >> 1) * 32 + (r & 31);
+    if (GATEUP) {  // 16-row blocks alternate gate, up, gate, up ... of the same output columns
+      const int jb = r >> 4;
+      wrow = col0 + (jb >> 1) * 16 + (r & 15);
       if (jb & 1) base = B1;
     } else {
       wrow = col0 + r;
@@ -175,9 +191,6 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
     b_src[j] = base + (size_t)tc.expert * expert_stride + (size_t)wrow * K + c * 8;
   }
 
-  // DMA instruction `idx` of a k-tile: the B (weight) rows first -- they come from HBM for the
-  // first time and need the longest flight -- then the A rows, which are re-read by every column
-  // block and mostly hit in L2.
   constexpr int N_DMA = A_INST + B_INST;
   auto issue_dma = [&](int kt, int stage, auto idx_tag) {
     constexpr int idx = decltype(idx_tag)::value;
@@ -193,142 +206,119 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
     }
   };
 
-  const int a_row = wm * (BM / WM) + (lane & 31);
-  const int b_row = wn * (BN / WN) + (lane & 31);
-  const int kq = lane >> 5;
-  // operand `r` of a k16 step: r < TM is the A fragment of row block r, else a B fragment
-  auto read_frag = [&](int stage, int ks, auto r_tag, bf16x8(&af)[TM], bf16x8(&bfr)[TN]) {
-    constexpr int r = decltype(r_tag)::value;
-    const uint16_t* sa = smem + stage * STAGE;
-    const uint16_t* sb = sa + BM * BK;
-    const int c = ks * 2 + kq;
-    if constexpr (r < TM)
-      af[r] = *reinterpret_cast<const bf16x8*>(sa + lds_off(a_row + r * 32, c));
-    else
-      bfr[r - TM] = *reinterpret_cast<const bf16x8*>(sb + lds_off(b_row + (r - TM) * 32, c));
+  const int a_row = wm * (BM / WM) + (lane & 15);
+  const int b_row = wn * (BN / WN) + (lane & 15);
+  const int kq = lane >> 4;
+  bf16x8 af[TM][2], bfr[TN][2];
+  auto read_a = [&](int stage, auto i_tag, auto ks_tag) {
+    constexpr int i = decltype(i_tag)::value, ks = decltype(ks_tag)::value;
+    af[i][ks] = *reinterpret_cast<const bf16x8*>(smem + stage * STAGE + lds_off(a_row + i * 16, ks * 4 + kq));
+  };
+  auto read_b = [&](int stage, auto j_tag, auto ks_tag) {
+    constexpr int j = decltype(j_tag)::value, ks = decltype(ks_tag)::value;
+    bfr[j][ks] =
+        *reinterpret_cast<const bf16x8*>(smem + stage * STAGE + BM * BK + lds_off(b_row + j * 16, ks * 4 + kq));
   };
 
-  f32x16 acc[TM][TN];
+  f32x4 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   const int nk = K / BK;
-  bf16x8 af0[TM], bf0[TN], af1[TM], bf1[TN];
-  constexpr int NM = TM * TN, NDS = TM + TN;
-  constexpr int RD_SLOTS = NM * 3 / 4;
-
-  // One k16 step in a fixed instruction order: the NM MFMAs on the operands (af, bfr), and
-  // between them, evenly spread, (READS) the NDS reads of the next step's operands into (afn,
-  // bfn) from LDS stage rd_stage / step rd_ks, and the DMA instructions [DLO, DHI) of k-tile
-  // dma_kt into LDS stage dma_stage.  Each MFMA and the memory instructions that follow it are
-  // fenced, so the matrix pipe never waits behind a burst of memory instructions and the
-  // texture-address unit sees a steady stream of DMA requests that it can accept without
-  // stalling the wave.
-  auto k_step = [&](const bf16x8(&af)[TM], const bf16x8(&bfr)[TN], auto reads_tag, int rd_stage, int rd_ks,
-                    bf16x8(&afn)[TM], bf16x8(&bfn)[TN], auto dlo_tag, auto dhi_tag, int dma_kt, int dma_stage) {
-    constexpr bool READS = decltype(reads_tag)::value;
-    constexpr int DLO = decltype(dlo_tag)::value, NVM = decltype(dhi_tag)::value - DLO;
-    static_for<0, NM>([&](auto m_tag) {
-      constexpr int m = decltype(m_tag)::value;
-      constexpr int i = m / TN, j = m % TN;
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-      if constexpr (READS && m < RD_SLOTS) {  // operand reads finish early in the step
-        static_for<(m * NDS) / RD_SLOTS, ((m + 1) * NDS) / RD_SLOTS>(
-            [&](auto r_tag) { read_frag(rd_stage, rd_ks, r_tag, afn, bfn); });
-      }
-      static_for<DLO + (m * NVM) / NM, DLO + ((m + 1) * NVM) / NM>(
-          [&](auto d_tag) { issue_dma(dma_kt, dma_stage, d_tag); });
-      __builtin_amdgcn_sched_barrier(0);
-    });
-  };
-
-  // The DMA of a k-tile is issued in three slices over the three k16 steps that follow the
-  // release of its LDS stage; the fourth step gives the last slice time to land.
-  constexpr int D0 = (N_DMA * 3 + 7) / 8;        // right after the barrier (step 3 of tile kt)
-  constexpr int D1 = D0 + (N_DMA - D0 + 1) / 2;  // step 0 of tile kt+1; the rest in step 1
   using T_ = std::true_type;
   using F_ = std::false_type;
-  template_int<0> i0_;
-  template_int<D0> iD0_;
-  template_int<D1> iD1_;
-  template_int<N_DMA> iN_;
+  template_int<0> k0_;
+  template_int<1> k1_;
+  // DMA instruction d (0..N_DMA-1) goes after pair TN + d * DSPAN / N_DMA: spread over rows 1..TM-2
+  constexpr int DSPAN = (TM - 2) * TN;
 
-  // One k-tile.  L01: issue the rest of tile kt+1's DMA during steps 0 and 1.  SYNC: after the
-  // tile's last operand read, wait for tile kt+1, barrier, then (L3) start refilling the stage
-  // just consumed with tile kt+2 and prefetch tile kt+1's first operands, all overlapped with
-  // the last quarter of this tile's MFMAs.
-  auto k_tile = [&](int kt, auto l01_tag, auto sync_tag, auto l3_tag) {
-    constexpr bool L01 = decltype(l01_tag)::value, SYNC = decltype(sync_tag)::value, L3 = decltype(l3_tag)::value;
-    const int cur = kt & 1;
-    if constexpr (L01) {
-      k_step(af0, bf0, T_{}, cur, 1, af1, bf1, iD0_, iD1_, kt + 1, cur ^ 1);
-      k_step(af1, bf1, T_{}, cur, 2, af0, bf0, iD1_, iN_, kt + 1, cur ^ 1);
-    } else {
-      k_step(af0, bf0, T_{}, cur, 1, af1, bf1, i0_, i0_, 0, 0);
-      k_step(af1, bf1, T_{}, cur, 2, af0, bf0, i0_, i0_, 0, 0);
-    }
-    k_step(af0, bf0, T_{}, cur, 3, af1, bf1, i0_, i0_, 0, 0);
-    if constexpr (SYNC) {
-      wait_lgkmcnt0();  // my reads of stage `cur` are done
-      wait_vmcnt<0>();  // tile kt+1 has landed in the other stage
-      __builtin_amdgcn_s_barrier();
-      if constexpr (L3)
-        k_step(af1, bf1, T_{}, cur ^ 1, 0, af0, bf0, i0_, iD0_, kt + 2, cur);
-      else
-        k_step(af1, bf1, T_{}, cur ^ 1, 0, af0, bf0, i0_, i0_, 0, 0);
-    } else {
-      k_step(af1, bf1, F_{}, 0, 0, af0, bf0, i0_, i0_, 0, 0);
-    }
+  // One k-tile.  SYNC: barrier after row 0, then refresh from the next stage.  DMA: refill this
+  // tile's stage with tile kt+2 during rows 1..TM-2.
+  auto k_tile = [&](int kt, auto sync_tag, auto dma_tag) {
+    constexpr bool SYNC = decltype(sync_tag)::value, DMA = decltype(dma_tag)::value;
+    const int cur = kt & 1, nxt = cur ^ 1;
+    static_for<0, NP>([&](auto p_tag) {
+      constexpr int p = decltype(p_tag)::value;
+      constexpr int i = p / TN, j = p % TN;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i][0], bfr[j][0], acc[i][j], 0, 0, 0);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i][1], bfr[j][1], acc[i][j], 0, 0, 0);
+      if constexpr (i == 0 && j == 0) {  // A[TM-1] of THIS tile (registers still hold the previous tile's)
+        read_a(cur, template_int<TM - 1>{}, k0_);
+        read_a(cur, template_int<TM - 1>{}, k1_);
+      }
+      if constexpr (SYNC) {
+        if constexpr (i >= 1 && j == 0) {  // A[i-1] of the next tile
+          read_a(nxt, template_int<i - 1>{}, k0_);
+          read_a(nxt, template_int<i - 1>{}, k1_);
+        }
+        if constexpr (i == TM - 1) {  // B[j] of the next tile, right after its last use
+          read_b(nxt, template_int<j>{}, k0_);
+          read_b(nxt, template_int<j>{}, k1_);
+        }
+      }
+      if constexpr (DMA && i >= 1 && i <= TM - 2) {
+        constexpr int q = p - TN;
+        static_for<(q * N_DMA) / DSPAN, ((q + 1) * N_DMA) / DSPAN>(
+            [&](auto d_tag) { issue_dma(kt + 2, cur, d_tag); });
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (SYNC && p == TN - 1) {
+        wait_lgkmcnt0();  // my refresh reads of this tile's stage are done
+        wait_vmcnt<0>();  // tile kt+1 has landed in the other stage
+        __builtin_amdgcn_s_barrier();
+      }
+    });
   };
 
   static_for<0, N_DMA>([&](auto d_tag) { issue_dma(0, 0, d_tag); });
   wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
-  if (nk > 1) static_for<0, D0>([&](auto d_tag) { issue_dma(1, 1, d_tag); });
-  static_for<0, NDS>([&](auto r_tag) { read_frag(0, 0, r_tag, af0, bf0); });
-  for (int kt = 0; kt + 2 < nk; ++kt) k_tile(kt, T_{}, T_{}, T_{});
-  if (nk > 1) k_tile(nk - 2, T_{}, T_{}, F_{});
-  k_tile(nk - 1, F_{}, F_{}, F_{});
+  if (nk > 1) static_for<0, N_DMA>([&](auto d_tag) { issue_dma(1, 1, d_tag); });
+  static_for<0, TM>([&](auto i_tag) {
+    read_a(0, i_tag, k0_);
+    read_a(0, i_tag, k1_);
+  });
+  static_for<0, TN>([&](auto j_tag) {
+    read_b(0, j_tag, k0_);
+    read_b(0, j_tag, k1_);
+  });
+  for (int kt = 0; kt + 2 < nk; ++kt) k_tile(kt, T_{}, T_{});
+  if (nk > 1) k_tile(nk - 2, T_{}, F_{});
+  k_tile(nk - 1, F_{}, F_{});
 
-  // ---- epilogue
-  const int lcol = lane & 31;
+  // ---- epilogue: accumulator register v of a 16x16 tile is row (lane/16)*4 + v, column lane%16
+  const int lcol = lane & 15, lrow = (lane >> 4) * 4;
   const bool full = (row0 + BM <= hi) && (col0 + NCOLS <= n_out);
   auto store_tile = [&](auto guard) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-      const int rbase = row0 + wm * (BM / WM) + i * 32;
+      const int rbase = row0 + wm * (BM / WM) + i * 16 + lrow;
       if constexpr (GATEUP) {
 #pragma unroll
         for (int j = 0; j < TN; j += 2) {
           const int jb = wn * TN + j;  // even: gate block; jb + 1: up block of the same columns
-          const int col = col0 + (jb >> 1) * 32 + lcol;
+          const int col = col0 + (jb >> 1) * 16 + lcol;
           uint16_t* cp = reinterpret_cast<uint16_t*>(C) + (size_t)rbase * n_out + col;
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int ro = acc_row(v, lane);
-            if (guard(rbase + ro, col))
-              cp[(size_t)ro * n_out] = (uint16_t)f32_to_bf16_bits(silu_mul(acc[i][j][v], acc[i][j + 1][v]));
-          }
+          for (int v = 0; v < 4; ++v)
+            if (guard(rbase + v, col))
+              cp[(size_t)v * n_out] = (uint16_t)f32_to_bf16_bits(silu_mul(acc[i][j][v], acc[i][j + 1][v]));
         }
       } else {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-          const int col = col0 + wn * (BN / WN) + j * 32 + lcol;
+          const int col = col0 + wn * (BN / WN) + j * 16 + lcol;
           OutT* cp = C + (size_t)rbase * n_out + col;
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int ro = acc_row(v, lane);
-            if (guard(rbase + ro, col)) {
+          for (int v = 0; v < 4; ++v)
+            if (guard(rbase + v, col)) {
               if constexpr (sizeof(OutT) == 4)
-                cp[(size_t)ro * n_out] = acc[i][j][v];
+                cp[(size_t)v * n_out] = acc[i][j][v];
               else
-                cp[(size_t)ro * n_out] = (OutT)f32_to_bf16_bits(acc[i][j][v]);
+                cp[(size_t)v * n_out] = (OutT)f32_to_bf16_bits(acc[i][j][v]);
             }
-          }
         }
       }
     }
