@@ -196,7 +196,7 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import moe_oracle as O
-        n = args.cpu_sample_tokens or min(T, 512)
+        n = args.cpu_sample_tokens or min(T, 4096)
         sel = np.linspace(0, T - 1, n).astype(np.int64)
         lg = layer.logits[:T].cpu().numpy()[sel]
         shared = (li.ws_gate, li.ws_up, li.ws_down) if li.ws_gate is not None else None

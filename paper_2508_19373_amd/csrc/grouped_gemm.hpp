@@ -36,7 +36,7 @@ typedef __attribute__((address_space(1))) const void global_void_t;
 
 __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 __device__ __forceinline__ int lds_off(int row, int chunk) { return row * BK + ((chunk ^ swz(row)) << 3); }
-__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.f + __expf(-g)) * u; }
+__device__ __forceinline__ float silu_mul(float g, float u) { return g * __builtin_amdgcn_rcpf(1.f + __expf(-g)) * u; }
 
 // s_waitcnt with only vmcnt / only lgkmcnt constrained (gfx9 encoding)
 template <int N>
@@ -135,12 +135,7 @@ __device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ exper
 // fragments) and are refreshed in place: a fragment is re-read from the next k-tile's LDS stage
 // right after its last use.  LDS is then a two-stage landing buffer in front of the register
 // tile (a three-deep pipeline), still with one barrier per k-tile.
-// Order inside a k-tile: for row block i, for column block j: MFMA(k-half 0), MFMA(k-half 1).
-//   row 0        : refresh A[TM-1] from this tile's stage (its last use was the previous tile's end)
-//   barrier      : after row 0 -- every wave is done with the previous refreshes, tile kt+1 landed
-//   rows 1..TM-2 : DMA of tile kt+2 into the stage just freed, spread between the MFMA pairs
-//   row i >= 1   : refresh A[i-1] from tile kt+1's stage
-//   row TM-1     : refresh B[j] after its last use (i = TM-1)
+// The traversal order and the refresh schedule are described at k_tile below.
 template <int BM, int BN, int WM, int WN, bool GATEUP, typename OutT>
 __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, const uint16_t* __restrict__ A,
                                             int cap_rows, const uint16_t* __restrict__ B0,
@@ -231,41 +226,55 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
   using F_ = std::false_type;
   template_int<0> k0_;
   template_int<1> k1_;
-  // DMA instruction d (0..N_DMA-1) goes after pair TN + d * DSPAN / N_DMA: spread over rows 1..TM-2
-  constexpr int DSPAN = (TM - 2) * TN;
+  // DMA instruction d (0..N_DMA-1) goes after pair TN + d * DSPAN / N_DMA: the 3/4 of the tile after
+  // the barrier, which leaves the last instructions a quarter tile to land
+  constexpr int DSPAN = (NP - TN) * 3 / 4;
 
-  // One k-tile.  SYNC: barrier after row 0, then refresh from the next stage.  DMA: refill this
-  // tile's stage with tile kt+2 during rows 1..TM-2.
+  // One k-tile.  SYNC: barrier after the first row, then refresh from the next stage.  DMA: refill
+  // this tile's stage with tile kt+2, one instruction every few pairs.
+  // Pair order: the upper half of the row blocks row by row, the lower half column by column, so
+  // operand fragments die -- and are refreshed -- at an even pace (at most 2 LDS reads per pair;
+  // reading all B fragments in the last row made that row LDS-bound):
+  //   pair p < TM            : A[TM/2 + p/2][p%2] of THIS tile (lower-half A rows die at the tile's end)
+  //   end of upper row i     : A[i] of the next tile
+  //   end of lower column j  : B[j] of the next tile
+  constexpr int HM = TM / 2, NP1 = HM * TN;
+  static_assert(TM % 2 == 0 && TN >= TM, "pair order needs an even row-block count and TN >= TM");
   auto k_tile = [&](int kt, auto sync_tag, auto dma_tag) {
     constexpr bool SYNC = decltype(sync_tag)::value, DMA = decltype(dma_tag)::value;
     const int cur = kt & 1, nxt = cur ^ 1;
     static_for<0, NP>([&](auto p_tag) {
       constexpr int p = decltype(p_tag)::value;
-      constexpr int i = p / TN, j = p % TN;
-      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i][0], bfr[j][0], acc[i][j], 0, 0, 0);
-      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i][1], bfr[j][1], acc[i][j], 0, 0, 0);
-      if constexpr (i == 0 && j == 0) {  // A[TM-1] of THIS tile (registers still hold the previous tile's)
-        read_a(cur, template_int<TM - 1>{}, k0_);
-        read_a(cur, template_int<TM - 1>{}, k1_);
-      }
+      constexpr bool upper = p < NP1;
+      constexpr int i = upper ? p / TN : HM + (p - NP1) % HM;
+      constexpr int j = upper ? p % TN : (p - NP1) / HM;
+      // weights as the MFMA "A" operand, activations as "B": the result tile is the transpose, so a
+      // lane ends up with 4 CONSECUTIVE output columns of one row (one 8- or 16-byte store)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[j][0], af[i][0], acc[i][j], 0, 0, 0);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[j][1], af[i][1], acc[i][j], 0, 0, 0);
+      if constexpr (p < TM) read_a(cur, template_int<HM + p / 2>{}, template_int<p % 2>{});
       if constexpr (SYNC) {
-        if constexpr (i >= 1 && j == 0) {  // A[i-1] of the next tile
-          read_a(nxt, template_int<i - 1>{}, k0_);
-          read_a(nxt, template_int<i - 1>{}, k1_);
+        if constexpr (upper && j == TN - 1 && p >= TN) {  // rows 1..HM-1: after the barrier
+          read_a(nxt, template_int<i>{}, k0_);
+          read_a(nxt, template_int<i>{}, k1_);
         }
-        if constexpr (i == TM - 1) {  // B[j] of the next tile, right after its last use
+        if constexpr (p == TN + 1) {  // row 0 died before the barrier: refresh it right after
+          read_a(nxt, template_int<0>{}, k0_);
+          read_a(nxt, template_int<0>{}, k1_);
+        }
+        if constexpr (!upper && i == TM - 1) {
           read_b(nxt, template_int<j>{}, k0_);
           read_b(nxt, template_int<j>{}, k1_);
         }
       }
-      if constexpr (DMA && i >= 1 && i <= TM - 2) {
+      if constexpr (DMA && p >= TN && p < TN + DSPAN) {
         constexpr int q = p - TN;
         static_for<(q * N_DMA) / DSPAN, ((q + 1) * N_DMA) / DSPAN>(
             [&](auto d_tag) { issue_dma(kt + 2, cur, d_tag); });
       }
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (SYNC && p == TN - 1) {
-        wait_lgkmcnt0();  // my refresh reads of this tile's stage are done
+        wait_lgkmcnt0();  // my reads of this tile's stage are done
         wait_vmcnt<0>();  // tile kt+1 has landed in the other stage
         __builtin_amdgcn_s_barrier();
       }
@@ -288,37 +297,41 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
   if (nk > 1) k_tile(nk - 2, T_{}, F_{});
   k_tile(nk - 1, F_{}, F_{});
 
-  // ---- epilogue: accumulator register v of a 16x16 tile is row (lane/16)*4 + v, column lane%16
-  const int lcol = lane & 15, lrow = (lane >> 4) * 4;
-  const bool full = (row0 + BM <= hi) && (col0 + NCOLS <= n_out);
+  // ---- epilogue: accumulator register v of tile (i, j) is row i*16 + lane%16, column
+  // j*16 + (lane/16)*4 + v of the wave's sub-tile
+  const int lrow = lane & 15, lcol = (lane >> 4) * 4;
+  const bool full = (row0 + BM <= hi) && (col0 + NCOLS <= n_out);  // n_out is a multiple of 4
   auto store_tile = [&](auto guard) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-      const int rbase = row0 + wm * (BM / WM) + i * 16 + lrow;
+      const int row = row0 + wm * (BM / WM) + i * 16 + lrow;
       if constexpr (GATEUP) {
 #pragma unroll
         for (int j = 0; j < TN; j += 2) {
           const int jb = wn * TN + j;  // even: gate block; jb + 1: up block of the same columns
           const int col = col0 + (jb >> 1) * 16 + lcol;
-          uint16_t* cp = reinterpret_cast<uint16_t*>(C) + (size_t)rbase * n_out + col;
-#pragma unroll
-          for (int v = 0; v < 4; ++v)
-            if (guard(rbase + v, col))
-              cp[(size_t)v * n_out] = (uint16_t)f32_to_bf16_bits(silu_mul(acc[i][j][v], acc[i][j + 1][v]));
+          if (guard(row, col)) {
+            uint2 o;
+            o.x = pack_bf16x2(silu_mul(acc[i][j][0], acc[i][j + 1][0]), silu_mul(acc[i][j][1], acc[i][j + 1][1]));
+            o.y = pack_bf16x2(silu_mul(acc[i][j][2], acc[i][j + 1][2]), silu_mul(acc[i][j][3], acc[i][j + 1][3]));
+            *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(C) + (size_t)row * n_out + col) = o;
+          }
         }
       } else {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           const int col = col0 + wn * (BN / WN) + j * 16 + lcol;
-          OutT* cp = C + (size_t)rbase * n_out + col;
-#pragma unroll
-          for (int v = 0; v < 4; ++v)
-            if (guard(rbase + v, col)) {
-              if constexpr (sizeof(OutT) == 4)
-                cp[(size_t)v * n_out] = acc[i][j][v];
-              else
-                cp[(size_t)v * n_out] = (OutT)f32_to_bf16_bits(acc[i][j][v]);
+          if (guard(row, col)) {
+            if constexpr (sizeof(OutT) == 4) {
+              *reinterpret_cast<float4*>(C + (size_t)row * n_out + col) =
+                  make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+            } else {
+              uint2 o;
+              o.x = pack_bf16x2(acc[i][j][0], acc[i][j][1]);
+              o.y = pack_bf16x2(acc[i][j][2], acc[i][j][3]);
+              *reinterpret_cast<uint2*>(C + (size_t)row * n_out + col) = o;
             }
+          }
         }
       }
     }

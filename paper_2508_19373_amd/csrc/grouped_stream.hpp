@@ -28,7 +28,7 @@ constexpr int kWaves = 4;
 constexpr int U = 4;         // k32 steps per operand register set
 constexpr int kMaxMT = 2;    // 16-row activation tiles handled per pass
 
-__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.f + __expf(-g)) * u; }
+__device__ __forceinline__ float silu_mul(float g, float u) { return g * __builtin_amdgcn_rcpf(1.f + __expf(-g)) * u; }
 
 // Rows [row_lo, row_hi) (at most 16*MT) of one expert against one 16-feature strip.
 // red: kWaves * MT * 256 floats of LDS.

@@ -23,7 +23,7 @@
 namespace moe {
 namespace gw {
 
-__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.f + __expf(-g)) * u; }
+__device__ __forceinline__ float silu_mul(float g, float u) { return g * __builtin_amdgcn_rcpf(1.f + __expf(-g)) * u; }
 
 template <int LO, int HI, typename F>
 __device__ __forceinline__ void static_for(F&& f) {

@@ -20,7 +20,9 @@ __global__ __launch_bounds__(kIdxThreads) void permute_index_kernel(const int32_
                                                                    int n_local, int offset,
                                                                    int32_t* __restrict__ expert_offsets,
                                                                    int32_t* __restrict__ row_src,
-                                                                   int32_t* __restrict__ slot_row) {
+                                                                   int32_t* __restrict__ slot_row,
+                                                                   const uint4* __restrict__ x, int k,
+                                                                   int chunks_per_row, uint4* __restrict__ x_perm) {
   __shared__ int32_t base[MOE_MAX_EXPERTS];                   // next free row of each expert
   __shared__ int32_t wave_cnt[kIdxWaves][MOE_MAX_EXPERTS];    // per-wave counts, then per-wave bases
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
@@ -94,6 +96,15 @@ __global__ __launch_bounds__(kIdxThreads) void permute_index_kernel(const int32_
       }
     }
     __syncthreads();
+  }
+  // decode-sized batches: the same workgroup also gathers the rows (x != nullptr), saving a launch
+  if (x != nullptr) {
+    const int R = base[n_local - 1];  // after the last chunk, base[e] is the end of expert e's rows
+    const int total = R * chunks_per_row;
+    for (int i = tid; i < total; i += kIdxThreads) {
+      const int r = i / chunks_per_row, c = i - r * chunks_per_row;
+      x_perm[(size_t)r * chunks_per_row + c] = x[(size_t)(row_src[r] / k) * chunks_per_row + c];
+    }
   }
 }
 
@@ -214,9 +225,12 @@ hipError_t launch_permute(const void* x, const int32_t* topk_idx, int T, int k, 
   const int A = T * k;
   hipError_t err;
   if (A <= 2 * kIdxThreads) {  // small batch: one workgroup does it all in one launch
+    const bool fuse = (size_t)A * H * 2 <= (256u << 10);
     hipLaunchKernelGGL(permute_index_kernel, dim3(1), dim3(kIdxThreads), 0, stream, topk_idx, A, n_local, offset,
-                       expert_offsets, row_src, slot_row);
+                       expert_offsets, row_src, slot_row, fuse ? static_cast<const uint4*>(x) : nullptr, k, H / 8,
+                       static_cast<uint4*>(x_perm));
     err = hipGetLastError();
+    if (fuse) return err;
   } else {
     const int blocks = (A + kIdxThreads - 1) / kIdxThreads;
     int32_t* counts = static_cast<int32_t*>(workspace);

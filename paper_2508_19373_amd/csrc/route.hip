@@ -12,6 +12,60 @@ constexpr int kRouteThreads = 256;
 constexpr int kTokPerBlock = kRouteThreads / kWave;
 constexpr int kExpChunk = 8;  // experts accumulated per pass over the token's row
 
+// Top-K selection and gate weights of one token by one wavefront.  myl[s] holds the logit of
+// expert lane + 64*s (-inf past E).  k rounds of wave-wide arg-max on (logit desc, expert id asc),
+// then softmax over all E logits evaluated at the selected ones.
+template <int EPL>
+__device__ __forceinline__ void select_topk(const float (&myl)[EPL], int lane, int E, int k, uint32_t flags,
+                                            int32_t* __restrict__ idx_out, float* __restrict__ w_out) {
+  uint32_t taken = 0;  // bit s set: this lane's slot s already selected
+  float sel_v = 0.f;
+  int sel_i = 0;
+  float vmax = 0.f;
+  for (int j = 0; j < k; ++j) {
+    float bv = -INFINITY;
+    int bi = 0x7FFFFFFF;
+#pragma unroll
+    for (int s = 0; s < EPL; ++s) {
+      const int e = lane + s * kWave;
+      if (e < E && !(taken & (1u << s)) && (myl[s] > bv || bi == 0x7FFFFFFF)) {
+        bv = myl[s];
+        bi = e;
+      }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const float ov = __shfl_xor(bv, o, kWave);
+      const int oi = __shfl_xor(bi, o, kWave);
+      const bool take = (oi != 0x7FFFFFFF) && (bi == 0x7FFFFFFF || ov > bv || (ov == bv && oi < bi));
+      if (take) {
+        bv = ov;
+        bi = oi;
+      }
+    }
+    if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
+    if (j == 0) vmax = bv;
+    if (lane == j) {
+      sel_v = bv;
+      sel_i = bi;
+    }
+  }
+  // softmax denominator over all E experts (max logit is the first selected one)
+  float part = 0.f;
+#pragma unroll
+  for (int s = 0; s < EPL; ++s) {
+    const int e = lane + s * kWave;
+    if (e < E) part += expf(myl[s] - vmax);
+  }
+  const float denom_all = wave_sum(part);
+  const float num = (lane < k) ? expf(sel_v - vmax) : 0.f;
+  const float denom_sel = wave_sum(num);
+  if (lane < k) {
+    idx_out[lane] = sel_i;
+    w_out[lane] = num / ((flags & MOE_RENORM_TOPK) ? denom_sel : denom_all);
+  }
+}
+
 template <int EPL>  // expert slots per lane: ceil(E / 64)
 __global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(
     const uint16_t* __restrict__ x, const float* __restrict__ w_router, float* __restrict__ logits, int T, int H, int E,
@@ -67,55 +121,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(
     }
   }
 
-  // k rounds of wave-wide arg-max on (logit desc, expert id asc)
-  uint32_t taken = 0;  // bit s set: this lane's slot s already selected
-  float sel_v = 0.f;
-  int sel_i = 0;
-  float vmax = 0.f;
-  for (int j = 0; j < k; ++j) {
-    float bv = -INFINITY;
-    int bi = 0x7FFFFFFF;
-#pragma unroll
-    for (int s = 0; s < EPL; ++s) {
-      const int e = lane + s * kWave;
-      if (e < E && !(taken & (1u << s)) && (myl[s] > bv || bi == 0x7FFFFFFF)) {
-        bv = myl[s];
-        bi = e;
-      }
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const float ov = __shfl_xor(bv, o, kWave);
-      const int oi = __shfl_xor(bi, o, kWave);
-      const bool take = (oi != 0x7FFFFFFF) && (bi == 0x7FFFFFFF || ov > bv || (ov == bv && oi < bi));
-      if (take) {
-        bv = ov;
-        bi = oi;
-      }
-    }
-    if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
-    if (j == 0) vmax = bv;
-    if (lane == j) {
-      sel_v = bv;
-      sel_i = bi;
-    }
-  }
-
-  // softmax denominator over all E experts (max logit is the first selected one)
-  float part = 0.f;
-#pragma unroll
-  for (int s = 0; s < EPL; ++s) {
-    const int e = lane + s * kWave;
-    if (e < E) part += expf(myl[s] - vmax);
-  }
-  const float denom_all = wave_sum(part);
-  const float num = (lane < k) ? expf(sel_v - vmax) : 0.f;
-  const float denom_sel = wave_sum(num);
-  if (lane < k) {
-    const float w = num / ((flags & MOE_RENORM_TOPK) ? denom_sel : denom_all);
-    topk_idx[(size_t)t * k + lane] = sel_i;
-    topk_w[(size_t)t * k + lane] = w;
-  }
+  select_topk<EPL>(myl, lane, E, k, flags, topk_idx + (size_t)t * k, topk_w + (size_t)t * k);
 }
 
 // Router logits as a small fp32 MFMA GEMM: logits[16 tokens, 16 experts] tiles with
@@ -123,7 +129,8 @@ __global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(
 // [H,E] row-major = the B operand's natural k-major form).  A workgroup owns 16 tokens; its NWV
 // wavefronts split the hidden dimension in 32-wide chunks (UNR chunks' loads are issued before
 // their MFMAs, so a decode-sized call is a couple of memory round trips, not one per chunk) and
-// the partial tiles are summed in wave order through LDS.  The sum over k may be taken in any
+// the partial tiles are summed in wave order through LDS; the same workgroup then selects the
+// top k of its 16 tokens from the logits tile, one wavefront per token.  The sum over k may be taken in any
 // order, so one 16-byte load per lane feeds 8 MFMAs: in MFMA s, lane (m, kq) supplies
 // x[t0+m, c*32 + kq*8 + s] and the B lane (n, kq) the matching W_r row.
 constexpr int kLogitTok = 16;
@@ -131,8 +138,12 @@ constexpr int kLogitTok = 16;
 template <int NT, int NWV, int UNR>  // 16-expert column tiles, wavefronts, chunks in flight per wavefront
 __global__ __launch_bounds__(NWV * 64) void router_logits_kernel(const uint16_t* __restrict__ x,
                                                                  const float* __restrict__ w_router,
-                                                                 float* __restrict__ logits, int T, int H, int E) {
+                                                                 float* __restrict__ logits, int T, int H, int E,
+                                                                 int k, uint32_t flags,
+                                                                 int32_t* __restrict__ topk_idx,
+                                                                 float* __restrict__ topk_w) {
   __shared__ float part[NWV][NT][16][17];
+  __shared__ float tile[16][NT * 16 + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int t0 = blockIdx.x * kLogitTok;
   const int m = lane & 15, kq = lane >> 4;
@@ -174,19 +185,33 @@ __global__ __launch_bounds__(NWV * 64) void router_logits_kernel(const uint16_t*
   for (int idx = tid; idx < NT * 256; idx += NWV * 64) {
     const int nt = idx >> 8, row = (idx >> 4) & 15, col = idx & 15;
     const int e = nt * 16 + col, t = t0 + row;
-    if (e < E && t < T) {
-      float sum = 0.f;
+    float sum = 0.f;
 #pragma unroll
-      for (int w = 0; w < NWV; ++w) sum += part[w][nt][row][col];
-      logits[(size_t)t * E + e] = sum;
+    for (int w = 0; w < NWV; ++w) sum += part[w][nt][row][col];
+    tile[row][nt * 16 + col] = sum;
+    if (e < E && t < T) logits[(size_t)t * E + e] = sum;
+  }
+  __syncthreads();
+  // selection: one wavefront per token, straight from the logits tile in LDS
+  constexpr int EPL = (NT * 16 + kWave - 1) / kWave;
+  for (int row = wave; row < 16; row += NWV) {
+    const int t = t0 + row;
+    if (t >= T) break;
+    float myl[EPL];
+#pragma unroll
+    for (int s = 0; s < EPL; ++s) {
+      const int e = lane + s * kWave;
+      myl[s] = (e < E) ? tile[row][e] : -INFINITY;
     }
+    select_topk<EPL>(myl, lane, E, k, flags, topk_idx + (size_t)t * k, topk_w + (size_t)t * k);
   }
 }
 
 template <int NT, int NWV, int UNR>
-void launch_logits(const uint16_t* x, const float* w_router, float* logits, int T, int H, int E, hipStream_t stream) {
+void launch_logits(const uint16_t* x, const float* w_router, float* logits, int T, int H, int E, int k, uint32_t flags,
+                   int32_t* topk_idx, float* topk_w, hipStream_t stream) {
   hipLaunchKernelGGL((router_logits_kernel<NT, NWV, UNR>), dim3((T + kLogitTok - 1) / kLogitTok), dim3(NWV * 64), 0,
-                     stream, x, w_router, logits, T, H, E);
+                     stream, x, w_router, logits, T, H, E, k, flags, topk_idx, topk_w);
 }
 
 }  // namespace
@@ -197,16 +222,14 @@ hipError_t launch_route_topk(const void* x, const float* w_router, float* logits
   const dim3 grid((T + kTokPerBlock - 1) / kTokPerBlock), block(kRouteThreads);
   const uint16_t* xs = static_cast<const uint16_t*>(x);
   if (!(flags & MOE_LOGITS_GIVEN) && H % 32 == 0) {
-    // logits by MFMA first, then the selection kernel reads them back as given logits
+    // logits by MFMA and the selection from the logits tile, in one kernel
     const int nt = (E + 15) / 16;
-    if (nt <= 1) launch_logits<1, 16, 4>(xs, w_router, logits, T, H, E, stream);
-    else if (nt <= 2) launch_logits<2, 16, 4>(xs, w_router, logits, T, H, E, stream);
-    else if (nt <= 4) launch_logits<4, 16, 2>(xs, w_router, logits, T, H, E, stream);
-    else if (nt <= 8) launch_logits<8, 8, 1>(xs, w_router, logits, T, H, E, stream);
-    else launch_logits<16, 4, 1>(xs, w_router, logits, T, H, E, stream);
-    const hipError_t err = hipGetLastError();
-    if (err != hipSuccess) return err;
-    flags |= MOE_LOGITS_GIVEN;
+    if (nt <= 1) launch_logits<1, 16, 4>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
+    else if (nt <= 2) launch_logits<2, 16, 4>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
+    else if (nt <= 4) launch_logits<4, 16, 2>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
+    else if (nt <= 8) launch_logits<8, 8, 1>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
+    else launch_logits<16, 4, 1>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
+    return hipGetLastError();
   }
   const int epl = (E + kWave - 1) / kWave;
   switch (epl) {
