@@ -47,21 +47,7 @@ WORKLOADS = {
 }
 
 
-def algorithmic_work(shape, T, counts):
-    """FLOPs and minimum HBM bytes the method itself needs for one layer on this shard
-    (never padded tiles, never inactive experts)."""
-    H, E, I_s = shape.hidden, shape.n_experts, shape.inter_slice
-    R = int(sum(counts))
-    active = int(sum(1 for c in counts if c > 0))
-    flops = 6.0 * R * H * I_s
-    if shape.router != "zipf":
-        flops += 2.0 * T * H * E
-    wbytes = 3.0 * H * I_s * 2 * active
-    if shape.inter_shared:
-        flops += 6.0 * T * H * shape.inter_shared_slice + 2.0 * T * H
-        wbytes += 3.0 * H * shape.inter_shared_slice * 2
-    bytes_ = wbytes + H * E * 4 + 2.0 * T * H * 2
-    return flops, bytes_, R, active
+from paper_2508_19373_amd.work import algorithmic_work  # noqa: E402
 
 
 def time_events(fn, iters, torch):
@@ -176,7 +162,7 @@ def main():
     g1_flops = 4.0 * R * H * I_s
     g1_bytes = 2.0 * active * H * I_s * 2 + R * H * 2 + R * I_s * 2
     intensity = g1_flops / g1_bytes
-    decode = (T * k) // shape.n_local_experts <= 40
+    decode = (T * k) // shape.n_local_experts <= 20
     kname = ("moe::gw::grouped_walk_kernel<..., GATEUP> (GEMM1 + SwiGLU, weight streaming)" if decode
              else "moe::gg::grouped_gemm_dlds_kernel<256, GATEUP> (GEMM1 + SwiGLU)")
     if intensity > PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):

@@ -128,7 +128,7 @@ hipError_t launch_pair_decode(const void* x_perm, const int32_t* expert_offsets,
   return hipGetLastError();
 }
 
-inline bool decode_regime(int cap_rows, int n_local) { return cap_rows / n_local <= 40; }
+inline bool decode_regime(int cap_rows, int n_local) { return cap_rows / n_local <= 20; }
 
 }  // namespace
 

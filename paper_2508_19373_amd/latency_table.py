@@ -1,0 +1,100 @@
+"""Operator benchmarking protocol for the Expert module: sweep (model shape, TP/EP shard, tokens)
+on the GPU and write the measured per-layer latency table T_e that the compute-simulation model
+is fitted on (paper, Sec. III-B "Inference Latency Estimation": the regressors' training sets
+are measured operator latencies; Sec. III-C: T_e is the Expert module's cost vector over the
+strategies of the search space, TP degree a power of two, EP degree dividing the expert count).
+
+    python -m paper_2508_19373_amd.latency_table --out profiles/expert_latency_table_mi355x.csv
+"""
+from __future__ import annotations
+
+import argparse
+import csv
+import sys
+import time
+
+FIELDS = ["model", "hidden", "n_experts", "top_k", "inter", "inter_shared", "tp", "ep", "ep_rank", "tokens",
+          "routed_rows", "active_experts", "flops", "weight_bytes", "us_per_layer", "launch_mode"]
+
+DEFAULT_TOKENS = (16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512, 768, 1024, 1536, 2048, 3072, 4096, 6144, 8192)
+
+
+def legal_shards(shape, max_devices=8):
+    """(E_t, E_e) with E_t a power of two dividing I into slices the kernels support, E_e dividing E,
+    E_t * E_e <= max_devices, and no triple hybrid (the paper excludes DP for experts)."""
+    out = []
+    for tp in (1, 2, 4, 8):
+        for ep in (1, 2, 4, 8):
+            if tp * ep > max_devices or shape.n_experts % ep or shape.inter % tp:
+                continue
+            if (shape.inter // tp) % 64 or (shape.inter_shared and (shape.inter_shared // tp) % 64):
+                continue
+            out.append((tp, ep))
+    return out
+
+
+def measure(shape, tokens, seed=0, steps=30, warmup=15):
+    import numpy as np
+    import torch
+    from . import inputs as I
+    from .layer import ExpertShardLayer, bf16_tensor
+    from .work import algorithmic_work
+
+    li = I.make_layer_inputs(shape, 1, seed)
+    layer = ExpertShardLayer.from_inputs(li, max_tokens=max(tokens))
+    rows = []
+    for T in tokens:
+        x = bf16_tensor(I.make_x(seed, T, shape.hidden))
+        logits = None
+        if shape.router == "zipf":
+            logits = torch.from_numpy(I.make_zipf_logits(seed, T, shape.n_experts)).cuda()
+
+        def timed(fn):
+            for _ in range(warmup):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e6 / steps
+
+        us, mode = timed(lambda: layer.forward(x, logits)), "eager"
+        if us < 1000.0:
+            graph, _ = layer.capture(x, logits)
+            us, mode = timed(graph.replay), "hip-graph"
+        counts = np.diff(layer.expert_offsets.cpu().numpy())
+        flops, min_bytes, R, active = algorithmic_work(shape, T, counts)
+        rows.append(dict(model=shape.name, hidden=shape.hidden, n_experts=shape.n_experts, top_k=shape.top_k,
+                         inter=shape.inter, inter_shared=shape.inter_shared, tp=shape.tp_degree, ep=shape.ep_degree,
+                         ep_rank=shape.ep_rank, tokens=T, routed_rows=R, active_experts=active, flops=flops,
+                         weight_bytes=min_bytes, us_per_layer=round(us, 2), launch_mode=mode))
+        print(rows[-1], flush=True)
+    del layer
+    torch.cuda.empty_cache()
+    return rows
+
+
+def main():
+    from . import inputs as I
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--out", required=True)
+    ap.add_argument("--tokens", type=int, nargs="*", default=list(DEFAULT_TOKENS))
+    ap.add_argument("--models", nargs="*", default=["mixtral", "qwen"])
+    args = ap.parse_args()
+    bases = {"mixtral": I.MIXTRAL, "qwen": I.QWEN}
+    rows = []
+    for m in args.models:
+        base = bases[m]
+        for tp, ep in legal_shards(base):
+            shape = base.shard(tp_degree=tp, tp_rank=0, ep_degree=ep, ep_rank=0)
+            rows += measure(shape, args.tokens)
+    with open(args.out, "w", newline="") as f:
+        w = csv.DictWriter(f, fieldnames=FIELDS)
+        w.writeheader()
+        w.writerows(rows)
+    print("wrote %d rows to %s" % (len(rows), args.out))
+
+
+if __name__ == "__main__":
+    main()
