@@ -19,17 +19,19 @@
 //  * one barrier per k-tile; DMA issue and operand reads are spread between the MFMA pairs in a
 //    fixed, fenced order (a burst of DMA instructions stalls the wave on the address unit);
 //  * tile ids are remapped so that each of the 8 XCDs (which get workgroups round-robin) works
-//    on a contiguous run of tiles that share A and B panels in its own L2.
+//    on a contiguous run of tiles that share A and B panels in its own L2; remainder tiles are
+//    grouped into units that cost about one full tile, so concurrent tiles stay in k-lockstep
+//    (see find_unit).
 #pragma once
 #include <type_traits>
 
 #include "moe_internal.hpp"
+#include "unit_list.hpp"
 
 namespace moe {
 namespace gg {
 
 constexpr int BK = 64;          // K elements per LDS row (128 bytes, 8 chunks of 16 bytes)
-constexpr int kNumXcd = 8;
 
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef __attribute__((address_space(1))) const void global_void_t;
@@ -58,71 +60,19 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-// Row blocks of one expert: as many 256-row blocks as fit, then the remainder r is covered by
-// the cheapest of {64}, {128}, {128 + 64}, {256} rows, so the padding per expert is below 64
-// rows (padded rows are pure loss: only algorithmic FLOPs count).
-struct RowBlocks {
-  int n256, n128, n64;
-  __device__ __forceinline__ int total() const { return n256 + n128 + n64; }
-};
-__device__ __forceinline__ RowBlocks row_blocks(int rows) {
-  RowBlocks rb;
-  const int r = rows & 255;
-  rb.n256 = (rows >> 8) + (r > 192 ? 1 : 0);
-  rb.n128 = (r > 64 && r <= 192) ? 1 : 0;
-  rb.n64 = ((r > 0 && r <= 64) || (r > 128 && r <= 192)) ? 1 : 0;
-  return rb;
-}
-// Host-side upper bound on sum_e row_blocks(rows_e).total() given sum_e rows_e <= cap_rows.
-inline int max_row_blocks(int cap_rows, int n_local) { return cap_rows / 256 + 2 * n_local; }
+constexpr int kLdsBytes = 160 * 1024;
 
-struct TileCoord {
-  int expert, row0, row_end, nb, height;  // height: 256, 128 or 64
-  bool valid;
-};
-
-// Tile `lid` of the list: experts in order, inside an expert column blocks in order, inside a
-// column block the row blocks (row block fastest, so neighbours share the B panel and a run of
-// tiles covers all row blocks of a few column blocks).
-__device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ expert_offsets, int n_local,
-                                               int n_col_blocks, int bid) {
-  TileCoord t;
-  t.valid = false;
-  int total = 0;
-  for (int e = 0; e < n_local; ++e)
-    total += row_blocks(expert_offsets[e + 1] - expert_offsets[e]).total() * n_col_blocks;
-  // XCD remap: workgroup b runs on XCD b % 8; give XCD x the tiles [x*chunk, (x+1)*chunk)
-  const int chunk = (total + kNumXcd - 1) / kNumXcd;
-  const int xcd = bid % kNumXcd, slot = bid / kNumXcd;
-  if (slot >= chunk) return t;
-  int lid = xcd * chunk + slot;
-  if (lid >= total) return t;
-  for (int e = 0; e < n_local; ++e) {
-    const int lo = expert_offsets[e], hi = expert_offsets[e + 1];
-    const RowBlocks rb = row_blocks(hi - lo);
-    const int mbs = rb.total();
-    const int tiles = mbs * n_col_blocks;
-    if (lid < tiles) {
-      const int mi = lid % mbs;
-      t.expert = e;
-      t.nb = lid / mbs;
-      t.row_end = hi;
-      if (mi < rb.n256) {
-        t.height = 256;
-        t.row0 = lo + mi * 256;
-      } else if (mi < rb.n256 + rb.n128) {
-        t.height = 128;
-        t.row0 = lo + rb.n256 * 256;
-      } else {
-        t.height = 64;
-        t.row0 = lo + rb.n256 * 256 + rb.n128 * 128;
-      }
-      t.valid = true;
-      return t;
-    }
-    lid -= tiles;
-  }
-  return t;
+// DMA bookkeeping of gemm_tile.  Tile t issues, in this order, the activation loads of tile t+NSA
+// (A_INST instructions, if that tile exists) and the weight loads of tile t+NSB (B_INST, likewise).
+// Loads complete in issue order, so at the barrier of the tile that has `j` tiles after it, the
+// loads that may stay in flight are those issued after the youngest one the next tile needs.
+constexpr int dma_slack(int j, int NSA, int NSB, int A_INST, int B_INST) {
+  int n = 0;
+  // the next tile's activations were issued NSA-1 tiles ago; the weights of that group are younger
+  if (NSA < NSB && j - 1 + NSA >= NSB) n += B_INST;
+  for (int jt = j + NSA - 2; jt >= j + 1; --jt)  // whole groups of the tiles in between
+    n += (jt >= NSA ? A_INST : 0) + (jt >= NSB ? B_INST : 0);
+  return n;
 }
 
 // One (BM x BN) output tile, computed by the whole workgroup of WM x WN wavefronts, on
@@ -136,7 +86,7 @@ __device__ __forceinline__ TileCoord find_tile(const int32_t* __restrict__ exper
 // right after its last use.  LDS is then a two-stage landing buffer in front of the register
 // tile (a three-deep pipeline), still with one barrier per k-tile.
 // The traversal order and the refresh schedule are described at k_tile below.
-template <int BM, int BN, int WM, int WN, bool GATEUP, typename OutT>
+template <int BM, int BN, int WM, int WN, int NSA, int NSB, bool GATEUP, typename OutT>
 __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, const uint16_t* __restrict__ A,
                                             int cap_rows, const uint16_t* __restrict__ B0,
                                             const uint16_t* __restrict__ B1, int n_out, int K,
@@ -145,7 +95,9 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
   constexpr int TM = BM / WM / 16, TN = BN / WN / 16;
   constexpr int A_INST = BM / 8 / NW, B_INST = BN / 8 / NW;
   constexpr int NCOLS = GATEUP ? BN / 2 : BN;
-  constexpr int STAGE = (BM + BN) * BK;
+  constexpr int A_STAGE = BM * BK, B_STAGE = BN * BK;  // LDS: NSA activation stages, then NSB weight stages
+  static_assert(NSA >= 2 && NSA <= NSB, "activations need at least two stages and no more than the weights");
+  static_assert((NSA * A_STAGE + NSB * B_STAGE) * 2 <= kLdsBytes, "LDS budget");
   constexpr int NP = TM * TN;  // MFMA pairs per k-tile
   static_assert(BM % (WM * 16) == 0 && BN % (WN * 16) == 0, "tile / wave grid mismatch");
   static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "loader mismatch");
@@ -187,17 +139,18 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
   }
 
   constexpr int N_DMA = A_INST + B_INST;
-  auto issue_dma = [&](int kt, int stage, auto idx_tag) {
+  // DMA instruction `idx` of a k-tile's group: the activation rows first, then the weight rows
+  // (loads complete in issue order, and the activations are the operand needed soonest)
+  auto issue_dma = [&](int kt_a, int stage_a, int kt_b, int stage_b, auto idx_tag) {
     constexpr int idx = decltype(idx_tag)::value;
-    uint16_t* sa = smem + stage * STAGE;
-    uint16_t* sb = sa + BM * BK;
-    if constexpr (idx < B_INST) {
-      __builtin_amdgcn_global_load_lds((global_void_t*)(b_src[idx] + (size_t)kt * BK),
-                                       (lds_void_t*)(sb + (idx * NW + wave) * 8 * BK), 16, 0, 0);
+    if constexpr (idx < A_INST) {
+      __builtin_amdgcn_global_load_lds((global_void_t*)(a_src[idx] + (size_t)kt_a * BK),
+                                       (lds_void_t*)(smem + stage_a * A_STAGE + (idx * NW + wave) * 8 * BK), 16, 0, 0);
     } else {
-      constexpr int j = idx - B_INST;
-      __builtin_amdgcn_global_load_lds((global_void_t*)(a_src[j] + (size_t)kt * BK),
-                                       (lds_void_t*)(sa + (j * NW + wave) * 8 * BK), 16, 0, 0);
+      constexpr int j = idx - A_INST;
+      __builtin_amdgcn_global_load_lds(
+          (global_void_t*)(b_src[j] + (size_t)kt_b * BK),
+          (lds_void_t*)(smem + NSA * A_STAGE + stage_b * B_STAGE + (j * NW + wave) * 8 * BK), 16, 0, 0);
     }
   };
 
@@ -207,12 +160,12 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
   bf16x8 af[TM][2], bfr[TN][2];
   auto read_a = [&](int stage, auto i_tag, auto ks_tag) {
     constexpr int i = decltype(i_tag)::value, ks = decltype(ks_tag)::value;
-    af[i][ks] = *reinterpret_cast<const bf16x8*>(smem + stage * STAGE + lds_off(a_row + i * 16, ks * 4 + kq));
+    af[i][ks] = *reinterpret_cast<const bf16x8*>(smem + stage * A_STAGE + lds_off(a_row + i * 16, ks * 4 + kq));
   };
   auto read_b = [&](int stage, auto j_tag, auto ks_tag) {
     constexpr int j = decltype(j_tag)::value, ks = decltype(ks_tag)::value;
-    bfr[j][ks] =
-        *reinterpret_cast<const bf16x8*>(smem + stage * STAGE + BM * BK + lds_off(b_row + j * 16, ks * 4 + kq));
+    bfr[j][ks] = *reinterpret_cast<const bf16x8*>(smem + NSA * A_STAGE + stage * B_STAGE +
+                                                  lds_off(b_row + j * 16, ks * 4 + kq));
   };
 
   f32x4 acc[TM][TN];
@@ -226,12 +179,15 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
   using F_ = std::false_type;
   template_int<0> k0_;
   template_int<1> k1_;
-  // DMA instruction d (0..N_DMA-1) goes after pair TN + d * DSPAN / N_DMA: the 3/4 of the tile after
-  // the barrier, which leaves the last instructions a quarter tile to land
+  // DMA instruction d of a group goes after pair TN + d * DSPAN / (group size): the 3/4 of the tile
+  // after the barrier
   constexpr int DSPAN = (NP - TN) * 3 / 4;
 
-  // One k-tile.  SYNC: barrier after the first row, then refresh from the next stage.  DMA: refill
-  // this tile's stage with tile kt+2, one instruction every few pairs.
+  // One k-tile with `sa`, `sb` the LDS stages that hold its activations and weights.
+  // SYNC: barrier after the first row, then refresh the register operands from the next stages.
+  // DMA_A / DMA_B: refill this tile's stages with the activations of tile kt+NSA / the weights of
+  // tile kt+NSB, one instruction every few pairs.  SLACK: DMA instructions that may still be in
+  // flight at the barrier (those issued after the ones tile kt+1 needs; loads complete in order).
   // Pair order: the upper half of the row blocks row by row, the lower half column by column, so
   // operand fragments die -- and are refreshed -- at an even pace (at most 2 LDS reads per pair;
   // reading all B fragments in the last row made that row LDS-bound):
@@ -240,9 +196,13 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
   //   end of lower column j  : B[j] of the next tile
   constexpr int HM = TM / 2, NP1 = HM * TN;
   static_assert(TM % 2 == 0 && TN >= TM, "pair order needs an even row-block count and TN >= TM");
-  auto k_tile = [&](int kt, auto sync_tag, auto dma_tag) {
-    constexpr bool SYNC = decltype(sync_tag)::value, DMA = decltype(dma_tag)::value;
-    const int cur = kt & 1, nxt = cur ^ 1;
+  auto k_tile = [&](int kt, int sa, int sb, auto sync_tag, auto dma_a_tag, auto dma_b_tag, auto slack_tag) {
+    constexpr bool SYNC = decltype(sync_tag)::value;
+    constexpr bool DMA_A = decltype(dma_a_tag)::value, DMA_B = decltype(dma_b_tag)::value;
+    constexpr int SLACK = decltype(slack_tag)::value;
+    constexpr int ND = DMA_B ? N_DMA : (DMA_A ? A_INST : 0);
+    static_assert(DMA_A || !DMA_B, "weights are prefetched at least as deep as activations");
+    const int sa_n = (sa + 1 == NSA) ? 0 : sa + 1, sb_n = (sb + 1 == NSB) ? 0 : sb + 1;
     static_for<0, NP>([&](auto p_tag) {
       constexpr int p = decltype(p_tag)::value;
       constexpr bool upper = p < NP1;
@@ -252,39 +212,48 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
       // lane ends up with 4 CONSECUTIVE output columns of one row (one 8- or 16-byte store)
       acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[j][0], af[i][0], acc[i][j], 0, 0, 0);
       acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[j][1], af[i][1], acc[i][j], 0, 0, 0);
-      if constexpr (p < TM) read_a(cur, template_int<HM + p / 2>{}, template_int<p % 2>{});
+      if constexpr (p < TM) read_a(sa, template_int<HM + p / 2>{}, template_int<p % 2>{});
       if constexpr (SYNC) {
         if constexpr (upper && j == TN - 1 && p >= TN) {  // rows 1..HM-1: after the barrier
-          read_a(nxt, template_int<i>{}, k0_);
-          read_a(nxt, template_int<i>{}, k1_);
+          read_a(sa_n, template_int<i>{}, k0_);
+          read_a(sa_n, template_int<i>{}, k1_);
         }
         if constexpr (p == TN + 1) {  // row 0 died before the barrier: refresh it right after
-          read_a(nxt, template_int<0>{}, k0_);
-          read_a(nxt, template_int<0>{}, k1_);
+          read_a(sa_n, template_int<0>{}, k0_);
+          read_a(sa_n, template_int<0>{}, k1_);
         }
         if constexpr (!upper && i == TM - 1) {
-          read_b(nxt, template_int<j>{}, k0_);
-          read_b(nxt, template_int<j>{}, k1_);
+          read_b(sb_n, template_int<j>{}, k0_);
+          read_b(sb_n, template_int<j>{}, k1_);
         }
       }
-      if constexpr (DMA && p >= TN && p < TN + DSPAN) {
+      if constexpr (ND > 0 && p >= TN && p < TN + DSPAN) {
         constexpr int q = p - TN;
-        static_for<(q * N_DMA) / DSPAN, ((q + 1) * N_DMA) / DSPAN>(
-            [&](auto d_tag) { issue_dma(kt + 2, cur, d_tag); });
+        static_for<(q * ND) / DSPAN, ((q + 1) * ND) / DSPAN>(
+            [&](auto d_tag) { issue_dma(kt + NSA, sa, kt + NSB, sb, d_tag); });
       }
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (SYNC && p == TN - 1) {
-        wait_lgkmcnt0();  // my reads of this tile's stage are done
-        wait_vmcnt<0>();  // tile kt+1 has landed in the other stage
+        wait_lgkmcnt0();       // my reads of this tile's activation stage are done
+        wait_vmcnt<SLACK>();   // tile kt+1 has landed
         __builtin_amdgcn_s_barrier();
       }
     });
   };
+  auto next_a = [](int st) { return (st + 1 == NSA) ? 0 : st + 1; };
+  auto next_b = [](int st) { return (st + 1 == NSB) ? 0 : st + 1; };
 
-  static_for<0, N_DMA>([&](auto d_tag) { issue_dma(0, 0, d_tag); });
+  // prologue: tile 0, then the groups that tiles -(NSB-1) .. -1 would have issued, in their order
+  static_for<0, N_DMA>([&](auto d_tag) { issue_dma(0, 0, 0, 0, d_tag); });
   wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
-  if (nk > 1) static_for<0, N_DMA>([&](auto d_tag) { issue_dma(1, 1, d_tag); });
+  static_for<1 - NSB, 0>([&](auto t_tag) {
+    constexpr int t = decltype(t_tag)::value;
+    if constexpr (t + NSA > 0) {
+      if (t + NSA < nk) static_for<0, A_INST>([&](auto d_tag) { issue_dma(t + NSA, t + NSA, 0, 0, d_tag); });
+    }
+    if (t + NSB < nk) static_for<A_INST, N_DMA>([&](auto d_tag) { issue_dma(0, 0, t + NSB, t + NSB, d_tag); });
+  });
   static_for<0, TM>([&](auto i_tag) {
     read_a(0, i_tag, k0_);
     read_a(0, i_tag, k1_);
@@ -293,9 +262,22 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
     read_b(0, j_tag, k0_);
     read_b(0, j_tag, k1_);
   });
-  for (int kt = 0; kt + 2 < nk; ++kt) k_tile(kt, T_{}, T_{});
-  if (nk > 1) k_tile(nk - 2, T_{}, F_{});
-  k_tile(nk - 1, F_{}, F_{});
+  int sa = 0, sb = 0, kt = 0;
+  for (; kt + NSB < nk; ++kt) {  // steady state: both refills exist
+    k_tile(kt, sa, sb, T_{}, T_{}, T_{}, template_int<dma_slack(NSA + NSB, NSA, NSB, A_INST, B_INST)>{});
+    sa = next_a(sa);
+    sb = next_b(sb);
+  }
+  static_for<0, NSB - 1>([&](auto q_tag) {  // the last tiles but one: j tiles follow, no weight refill left
+    constexpr int j = NSB - 1 - decltype(q_tag)::value;
+    if (nk - 1 - j >= 0) {
+      k_tile(nk - 1 - j, sa, sb, T_{}, std::integral_constant<bool, (j >= NSA)>{}, F_{},
+             template_int<dma_slack(j, NSA, NSB, A_INST, B_INST)>{});
+      sa = next_a(sa);
+      sb = next_b(sb);
+    }
+  });
+  k_tile(nk - 1, sa, sb, F_{}, F_{}, F_{}, template_int<0>{});
 
   // ---- epilogue: accumulator register v of tile (i, j) is row i*16 + lane%16, column
   // j*16 + (lane/16)*4 + v of the wave's sub-tile
@@ -342,22 +324,33 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
     store_tile([&](int row, int col) { return row < hi && col < n_out; });
 }
 
-// Kernel: 256 threads (4 wavefronts); each workgroup computes one tile of the list, whose
-// height (256, 128 or 64 rows) selects the wave arrangement.
+// Kernel: 256 threads (4 wavefronts); each workgroup runs one work unit, whose height class
+// selects the wave arrangement.
 template <int BN, bool GATEUP, typename OutT>
 __global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
     const uint16_t* __restrict__ A, const int32_t* __restrict__ expert_offsets, int n_local, int cap_rows,
     const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1, int n_out, int K, OutT* __restrict__ C,
-    int n_col_blocks) {
-  __shared__ __attribute__((aligned(1024))) uint16_t smem[2 * (256 + BN) * BK];
-  const TileCoord tc = find_tile(expert_offsets, n_local, n_col_blocks, blockIdx.x);
-  if (!tc.valid) return;
-  if (tc.height == 256)
-    gemm_tile<256, BN, 2, 2, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, C);
-  else if (tc.height == 128)
-    gemm_tile<128, BN, 2, 2, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, C);
-  else
-    gemm_tile<64, BN, 1, 4, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, C);
+    int n_col_blocks, int small_group) {
+  __shared__ __attribute__((aligned(1024))) uint16_t smem[kLdsBytes / 2];
+  const ClassCounts cc = count_tiles(expert_offsets, n_local, n_col_blocks);
+  const Unit u = find_unit(cc, small_group, blockIdx.x);
+  if (u.count == 0) return;
+  if (u.cls == 0) {
+    const TileCoord tc = locate_tile(expert_offsets, n_local, n_col_blocks, 0, u.first);
+    gemm_tile<256, BN, 2, 2, 2, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, C);
+  } else if (u.cls == 1) {
+    for (int t = 0; t < u.count; ++t) {
+      if (t) __syncthreads();  // the previous tile's last LDS reads are done before the stage is refilled
+      const TileCoord tc = locate_tile(expert_offsets, n_local, n_col_blocks, 1, u.first + t);
+      gemm_tile<128, BN, 2, 2, 3, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, C);
+    }
+  } else {
+    for (int t = 0; t < u.count; ++t) {
+      if (t) __syncthreads();
+      const TileCoord tc = locate_tile(expert_offsets, n_local, n_col_blocks, 2, u.first + t);
+      gemm_tile<64, BN, 1, 4, 4, 4, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, C);
+    }
+  }
 }
 
 }  // namespace gg

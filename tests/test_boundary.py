@@ -19,8 +19,8 @@ def lib():
     return B.lib()
 
 
-def _declared_functions():
-    src = open(os.path.join(ROOT, "include", "moe_shard.h")).read()
+def _declared_functions(header="moe_shard.h"):
+    src = open(os.path.join(ROOT, "include", header)).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", src)))
 
@@ -30,6 +30,15 @@ def test_every_declared_symbol_is_exported(lib):
     assert set(names) == set(B.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
+
+
+def test_every_declared_debug_symbol_is_exported(lib):
+    names = _declared_functions("moe_shard_debug.h")
+    assert set(names) == set(B.DEBUG_EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+    src = open(os.path.join(ROOT, "include", "moe_shard_debug.h")).read()
+    assert int(re.search(r"MOE_DEBUG_UNIT_INTS\s+(\d+)", src).group(1)) == B.DEBUG_UNIT_INTS
 
 
 def test_header_constants_match_binding():
