@@ -11,7 +11,7 @@
 extern "C" {
 #endif
 
-#define MOE_DEBUG_UNIT_INTS 14
+#define MOE_DEBUG_UNIT_INTS 5
 
 /*
  * The work list of moe_expert_ffn's prefill-regime grouped GEMM for one routing: the expert
@@ -20,16 +20,14 @@ extern "C" {
  * same code on the host.
  * expert_offsets [n_local+1] int32 HOST, non-decreasing, first >= 0, last <= cap_rows
  * n_col_blocks   column blocks per row block (GEMM1: ceil(I_s/128), GEMM2: ceil(H/256))
- * small_group    1 or 3 = how many 64-row remainder tiles share a workgroup; 0 = the launcher's choice
  * units          [max_units][MOE_DEBUG_UNIT_INTS] int32 HOST, one record per workgroup:
- *                {tile height (256/128/64, 0 = idle), n_tiles (0..3), then per tile
- *                 expert, row0, row_end, column block}; a tile covers rows
- *                 [row0, min(row0 + height, row_end)) of its expert.
+ *                {tile height (256/128/64, 0 = no tile), local expert, row0, row_end, column block};
+ *                a tile covers rows [row0, min(row0 + height, row_end)) of its expert.
  * Returns the grid size (number of records written), or a negative MOE_ERR_* code
  * (MOE_ERR_WORKSPACE when max_units is too small).
  */
 int32_t moe_debug_gemm_units(const int32_t* expert_offsets, int32_t n_local, int32_t cap_rows,
-                             int32_t n_col_blocks, int32_t small_group, int32_t* units,
+                             int32_t n_col_blocks, int32_t* units,
                              int32_t max_units);
 
 #ifdef __cplusplus

@@ -28,7 +28,7 @@ MOE_MAX_TOPK = 16
 EXPORTS = ("moe_route_topk", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_workspace_bytes",
            "moe_ffn_workspace_bytes", "moe_status_string")
 DEBUG_EXPORTS = ("moe_debug_gemm_units",)
-DEBUG_UNIT_INTS = 14
+DEBUG_UNIT_INTS = 5
 
 
 class MoeShard(ctypes.Structure):
@@ -66,7 +66,7 @@ def lib() -> ctypes.CDLL:
         L.moe_ffn_workspace_bytes.restype = sz
         L.moe_status_string.argtypes = [ctypes.c_int]
         L.moe_status_string.restype = ctypes.c_char_p
-        L.moe_debug_gemm_units.argtypes = [vp, i32, i32, i32, i32, vp, i32]
+        L.moe_debug_gemm_units.argtypes = [vp, i32, i32, i32, vp, i32]
         L.moe_debug_gemm_units.restype = i32
         _lib = L
     return _lib
@@ -139,15 +139,15 @@ def moe_combine(y_perm, slot_row, topk_w, T, k, H, y_shared, x, w_shared_gate, y
                                             _ptr(x), _ptr(w_shared_gate), _ptr(y_out), flags, _stream(stream)))
 
 
-def moe_debug_gemm_units(expert_offsets, cap_rows, n_col_blocks, small_group=0):
+def moe_debug_gemm_units(expert_offsets, cap_rows, n_col_blocks):
     """Host-only: the prefill grouped GEMM's work list for one routing, as an int32 array
     [grid, DEBUG_UNIT_INTS] (see include/moe_shard_debug.h).  `expert_offsets` is a host sequence."""
     import numpy as np
     offs = np.ascontiguousarray(expert_offsets, dtype=np.int32)
     n_local = offs.size - 1
-    max_units = 8 * (((cap_rows // 256 + n_local) * n_col_blocks + 7) // 8 + (2 * n_local * n_col_blocks + 7) // 8)
+    max_units = 8 * (((cap_rows // 256 + n_local) * n_col_blocks + 7) // 8 + 2 * ((n_local * n_col_blocks + 7) // 8))
     out = np.zeros((max_units, DEBUG_UNIT_INTS), dtype=np.int32)
-    n = lib().moe_debug_gemm_units(offs.ctypes.data, n_local, cap_rows, n_col_blocks, small_group,
+    n = lib().moe_debug_gemm_units(offs.ctypes.data, n_local, cap_rows, n_col_blocks,
                                    out.ctypes.data, max_units)
     if n < 0:
         raise MoeError("moe_debug_gemm_units", n)

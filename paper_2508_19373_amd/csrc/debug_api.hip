@@ -5,32 +5,28 @@
 #include "unit_list.hpp"
 
 extern "C" int32_t moe_debug_gemm_units(const int32_t* expert_offsets, int32_t n_local, int32_t cap_rows,
-                                        int32_t n_col_blocks, int32_t small_group, int32_t* units,
+                                        int32_t n_col_blocks, int32_t* units,
                                         int32_t max_units) {
   using namespace moe::gg;
   if (expert_offsets == nullptr || units == nullptr || n_local < 1 || cap_rows < 0 || n_col_blocks < 1)
     return MOE_ERR_INVALID_ARG;
-  if (small_group != 0 && small_group != 1 && small_group != 3) return MOE_ERR_INVALID_ARG;
   for (int e = 0; e < n_local; ++e)
     if (expert_offsets[e] > expert_offsets[e + 1]) return MOE_ERR_INVALID_ARG;
   if (expert_offsets[0] < 0 || expert_offsets[n_local] > cap_rows) return MOE_ERR_INVALID_ARG;
-  const int group = small_group ? small_group : small_group_for(cap_rows, n_col_blocks);
   const int grid = max_grid(cap_rows, n_local, n_col_blocks);
   if (grid > max_units) return MOE_ERR_WORKSPACE;
   const ClassCounts cc = count_tiles(expert_offsets, n_local, n_col_blocks);
   for (int b = 0; b < grid; ++b) {
     int32_t* rec = units + (size_t)b * MOE_DEBUG_UNIT_INTS;
     for (int i = 0; i < MOE_DEBUG_UNIT_INTS; ++i) rec[i] = 0;
-    const Unit u = find_unit(cc, group, b);
-    rec[0] = u.count ? (u.cls == 0 ? 256 : (u.cls == 1 ? 128 : 64)) : 0;
-    rec[1] = u.count;
-    for (int t = 0; t < u.count; ++t) {
-      const TileCoord tc = locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.first + t);
-      rec[2 + 4 * t + 0] = tc.expert;
-      rec[2 + 4 * t + 1] = tc.row0;
-      rec[2 + 4 * t + 2] = tc.row_end;
-      rec[2 + 4 * t + 3] = tc.nb;
-    }
+    const Unit u = find_unit(cc, b);
+    if (u.cls < 0) continue;
+    const TileCoord tc = locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx);
+    rec[0] = u.cls == 0 ? 256 : (u.cls == 1 ? 128 : 64);
+    rec[1] = tc.expert;
+    rec[2] = tc.row0;
+    rec[3] = tc.row_end;
+    rec[4] = tc.nb;
   }
   return grid;
 }

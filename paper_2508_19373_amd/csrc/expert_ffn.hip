@@ -24,7 +24,6 @@ hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, i
                             int I_s, const void* w_gate, const void* w_up, const void* w_down, void* h_ws,
                             void* y_perm, uint32_t flags, hipStream_t stream) {
   const bool y_bf16 = (flags & MOE_Y_PERM_BF16) != 0;
-  auto small_group_for = [&](int ncb) { return gg::small_group_for(cap_rows, ncb); };
   const dim3 block(256);
   const uint16_t* xp = static_cast<const uint16_t*>(x_perm);
   uint16_t* hw = static_cast<uint16_t*>(h_ws);
@@ -33,7 +32,7 @@ hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, i
     const int ncb = (I_s + BN / 2 - 1) / (BN / 2);
     hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, true, uint16_t>), grid_for(ncb), block, 0, stream, xp,
                        expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_gate),
-                       static_cast<const uint16_t*>(w_up), I_s, H, hw, ncb, small_group_for(ncb));
+                       static_cast<const uint16_t*>(w_up), I_s, H, hw, ncb);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
   }
@@ -42,13 +41,11 @@ hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, i
   if (y_bf16)
     hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, uint16_t>), grid_for(ncb), block, 0, stream, hw,
                        expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_down),
-                       static_cast<const uint16_t*>(nullptr), H, I_s, static_cast<uint16_t*>(y_perm), ncb,
-                       small_group_for(ncb));
+                       static_cast<const uint16_t*>(nullptr), H, I_s, static_cast<uint16_t*>(y_perm), ncb);
   else
     hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, float>), grid_for(ncb), block, 0, stream, hw,
                        expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_down),
-                       static_cast<const uint16_t*>(nullptr), H, I_s, static_cast<float*>(y_perm), ncb,
-                       small_group_for(ncb));
+                       static_cast<const uint16_t*>(nullptr), H, I_s, static_cast<float*>(y_perm), ncb);
   return hipGetLastError();
 }
 

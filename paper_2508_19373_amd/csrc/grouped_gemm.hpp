@@ -19,9 +19,8 @@
 //  * one barrier per k-tile; DMA issue and operand reads are spread between the MFMA pairs in a
 //    fixed, fenced order (a burst of DMA instructions stalls the wave on the address unit);
 //  * tile ids are remapped so that each of the 8 XCDs (which get workgroups round-robin) works
-//    on a contiguous run of tiles that share A and B panels in its own L2; remainder tiles are
-//    grouped into units that cost about one full tile, so concurrent tiles stay in k-lockstep
-//    (see find_unit).
+//    on a contiguous run of tiles that share A and B panels in its own L2; remainder tiles run
+//    after all full tiles, so concurrent full tiles stay in k-lockstep (see find_unit).
 #pragma once
 #include <type_traits>
 
@@ -179,9 +178,9 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
   using F_ = std::false_type;
   template_int<0> k0_;
   template_int<1> k1_;
-  // DMA instruction d of a group goes after pair TN + d * DSPAN / (group size): the 3/4 of the tile
-  // after the barrier
-  constexpr int DSPAN = (NP - TN) * 3 / 4;
+  // DMA instruction d of a group goes after pair TN + d * DSPAN / (group size): spread over the
+  // whole tile after the barrier (a burst of DMA instructions stalls the wave on the address unit)
+  constexpr int DSPAN = NP - TN;
 
   // One k-tile with `sa`, `sb` the LDS stages that hold its activations and weights.
   // SYNC: barrier after the first row, then refresh the register operands from the next stages.
@@ -324,33 +323,23 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
     store_tile([&](int row, int col) { return row < hi && col < n_out; });
 }
 
-// Kernel: 256 threads (4 wavefronts); each workgroup runs one work unit, whose height class
-// selects the wave arrangement.
+// Kernel: 256 threads (4 wavefronts); each workgroup computes one tile, whose height class
+// selects the wave arrangement and the LDS stage counts.
 template <int BN, bool GATEUP, typename OutT>
 __global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
     const uint16_t* __restrict__ A, const int32_t* __restrict__ expert_offsets, int n_local, int cap_rows,
     const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1, int n_out, int K, OutT* __restrict__ C,
-    int n_col_blocks, int small_group) {
+    int n_col_blocks) {
   __shared__ __attribute__((aligned(1024))) uint16_t smem[kLdsBytes / 2];
-  const ClassCounts cc = count_tiles(expert_offsets, n_local, n_col_blocks);
-  const Unit u = find_unit(cc, small_group, blockIdx.x);
-  if (u.count == 0) return;
-  if (u.cls == 0) {
-    const TileCoord tc = locate_tile(expert_offsets, n_local, n_col_blocks, 0, u.first);
+  const Unit u = find_unit(count_tiles(expert_offsets, n_local, n_col_blocks), blockIdx.x);
+  if (u.cls < 0) return;
+  const TileCoord tc = locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx);
+  if (u.cls == 0)
     gemm_tile<256, BN, 2, 2, 2, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, C);
-  } else if (u.cls == 1) {
-    for (int t = 0; t < u.count; ++t) {
-      if (t) __syncthreads();  // the previous tile's last LDS reads are done before the stage is refilled
-      const TileCoord tc = locate_tile(expert_offsets, n_local, n_col_blocks, 1, u.first + t);
-      gemm_tile<128, BN, 2, 2, 3, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, C);
-    }
-  } else {
-    for (int t = 0; t < u.count; ++t) {
-      if (t) __syncthreads();
-      const TileCoord tc = locate_tile(expert_offsets, n_local, n_col_blocks, 2, u.first + t);
-      gemm_tile<64, BN, 1, 4, 4, 4, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, C);
-    }
-  }
+  else if (u.cls == 1)
+    gemm_tile<128, BN, 2, 2, 3, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, C);
+  else
+    gemm_tile<64, BN, 1, 4, 4, 4, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, C);
 }
 
 }  // namespace gg
