@@ -44,6 +44,8 @@ WORKLOADS = {
     "mixtral_ep4_cold": ("mixtral_ep4_cold", 8192, "mixtral-8x7b EP=4 shard experts 6-7, Zipf(1.2), T=8192 global"),
     "qwen_prefill": ("qwen", 4096, "qwen1.5-moe-a2.7b + shared expert T=4096"),
     "qwen_decode": ("qwen", 32, "qwen1.5-moe-a2.7b + shared expert T=32"),
+    "qwen2_57b_prefill": ("qwen2_57b", 4096, "qwen2-57b-a14b + shared expert T=4096"),
+    "qwen2_57b_decode": ("qwen2_57b", 32, "qwen2-57b-a14b + shared expert T=32"),
 }
 
 

@@ -71,10 +71,14 @@ bool launch_walk(const gw::WalkPlan& plan, const uint16_t* A, const int32_t* exp
   MOE_WALK(8, 16)
   MOE_WALK(8, 14)
   MOE_WALK(8, 11)
+  MOE_WALK(8, 10)
   MOE_WALK(8, 8)
   MOE_WALK(8, 7)
+  MOE_WALK(8, 5)
   MOE_WALK(4, 11)
+  MOE_WALK(4, 10)
   MOE_WALK(4, 8)
+  MOE_WALK(4, 5)
 #undef MOE_WALK
   return false;
 }

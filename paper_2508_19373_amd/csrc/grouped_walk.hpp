@@ -179,10 +179,11 @@ inline WalkPlan plan_for(int K) {
   const int steps32 = K / 32;
   if (K % 32 == 0) {
     const int nws[2] = {8, 4};
-    const int cand[5] = {16, 14, 11, 8, 7};
+    const int cand[7] = {16, 14, 11, 10, 8, 7, 5};
     for (int nw : nws)
       for (int st : cand) {
-        if (nw == 4 && !(st == 11 || st == 8)) continue;  // instantiated: (8,16) (8,14) (8,11) (8,8) (8,7) (4,11) (4,8)
+        // instantiated: (8,16) (8,14) (8,11) (8,10) (8,8) (8,7) (8,5) (4,11) (4,10) (4,8) (4,5)
+        if (nw == 4 && !(st == 11 || st == 10 || st == 8 || st == 5)) continue;
         if (steps32 % (nw * st) == 0) return WalkPlan{nw, st, steps32 / (nw * st)};
       }
   }

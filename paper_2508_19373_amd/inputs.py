@@ -4,7 +4,11 @@ This module holds no arithmetic of the method itself (no routing, no GEMM, no
 softmax): it only draws random tensors of the shapes the paper's workloads have
 (model table in the evaluation section: Mixtral-8x7B hidden 4096 / 8 experts /
 intermediate 14336, Qwen1.5-MoE-A2.7B hidden 2048 / 60 experts / intermediate
-1408) and encodes them as bf16.  Both the HIP path's tests and the CPU oracle's
+1408, Qwen2-57B-A14B hidden 3584 / 64 experts / intermediate 2560) and encodes
+them as bf16.  What that table leaves open (top-k, shared-expert size, gate
+renormalisation) follows the published model configurations: top-2 with
+renormalisation for Mixtral, top-4 plus a 5632-wide shared expert for
+Qwen1.5-MoE, top-8 plus a 20480-wide shared expert for Qwen2-57B-A14B.  Both the HIP path's tests and the CPU oracle's
 tests take their inputs from here; neither side's code lives here.
 
 bf16 tensors are carried as ``numpy.uint16`` bit patterns so that numpy (which
@@ -92,6 +96,7 @@ MIXTRAL_TP4 = replace(MIXTRAL, name="mixtral-8x7b-tp4", tp_degree=4, tp_rank=0)
 MIXTRAL_EP4_HOT = replace(MIXTRAL, name="mixtral-8x7b-ep4-hot", router="zipf", ep_degree=4, ep_rank=0)
 MIXTRAL_EP4_COLD = replace(MIXTRAL, name="mixtral-8x7b-ep4-cold", router="zipf", ep_degree=4, ep_rank=3)
 QWEN = MoEShape("qwen1.5-moe-a2.7b", 2048, 60, 4, 1408, False, inter_shared=5632)
+QWEN2_57B = MoEShape("qwen2-57b-a14b", 3584, 64, 8, 2560, False, inter_shared=20480)
 
 WORKLOADS: Dict[str, Tuple[MoEShape, Tuple[int, ...]]] = {
     "tiny": (TINY, (64,)),
@@ -100,6 +105,7 @@ WORKLOADS: Dict[str, Tuple[MoEShape, Tuple[int, ...]]] = {
     "mixtral_ep4_hot": (MIXTRAL_EP4_HOT, (8192,)),
     "mixtral_ep4_cold": (MIXTRAL_EP4_COLD, (8192,)),
     "qwen": (QWEN, (32, 4096)),
+    "qwen2_57b": (QWEN2_57B, (32, 4096)),
 }
 
 ZIPF_S = 1.2

@@ -20,14 +20,15 @@ DEFAULT_TOKENS = (16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512, 768, 1024, 15
 
 
 def legal_shards(shape, max_devices=8):
-    """(E_t, E_e) with E_t a power of two dividing I into slices the kernels support, E_e dividing E,
-    E_t * E_e <= max_devices, and no triple hybrid (the paper excludes DP for experts)."""
+    """(E_t, E_e) with E_t a power of two dividing I, E_e dividing E, E_t * E_e <= max_devices, and
+    no triple hybrid (the paper excludes DP for experts).  Slices that are not a multiple of 64 are
+    zero-padded by the layer."""
     out = []
     for tp in (1, 2, 4, 8):
         for ep in (1, 2, 4, 8):
             if tp * ep > max_devices or shape.n_experts % ep or shape.inter % tp:
                 continue
-            if (shape.inter // tp) % 64 or (shape.inter_shared and (shape.inter_shared // tp) % 64):
+            if shape.inter_shared % tp:
                 continue
             out.append((tp, ep))
     return out
@@ -80,9 +81,9 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", required=True)
     ap.add_argument("--tokens", type=int, nargs="*", default=list(DEFAULT_TOKENS))
-    ap.add_argument("--models", nargs="*", default=["mixtral", "qwen"])
+    ap.add_argument("--models", nargs="*", default=["mixtral", "qwen", "qwen2_57b"])
     args = ap.parse_args()
-    bases = {"mixtral": I.MIXTRAL, "qwen": I.QWEN}
+    bases = {"mixtral": I.MIXTRAL, "qwen": I.QWEN, "qwen2_57b": I.QWEN2_57B}
     rows = []
     for m in args.models:
         base = bases[m]

@@ -17,10 +17,32 @@ def bf16_bits(t: torch.Tensor) -> np.ndarray:
     return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
+FFN_ALIGN = 64  # moe_expert_ffn needs I_s % 64 == 0
+
+
+def _pad_inter(w_gate, w_up, w_down, inter_slice):
+    """Zero-pad an intermediate slice to the next multiple of FFN_ALIGN: extra gate/up rows and
+    down columns of zeros add silu(0) * 0 = 0 times 0 to every output, so results are unchanged
+    (memory plumbing for tensor-parallel slices such as 1408 / 4 = 352; no arithmetic here)."""
+    pad = -inter_slice % FFN_ALIGN
+    if pad == 0:
+        return w_gate, w_up, w_down, inter_slice
+    E, _, H = w_gate.shape
+    g = torch.zeros((E, inter_slice + pad, H), dtype=w_gate.dtype, device=w_gate.device)
+    u = torch.zeros_like(g)
+    d = torch.zeros((E, H, inter_slice + pad), dtype=w_down.dtype, device=w_down.device)
+    g[:, :inter_slice].copy_(w_gate)
+    u[:, :inter_slice].copy_(w_up)
+    d[:, :, :inter_slice].copy_(w_down)
+    return g, u, d, inter_slice + pad
+
+
 class ExpertShardLayer:
     """route -> permute -> expert FFN (-> shared expert FFN) -> combine, on the current stream.
 
-    Weights are torch.bfloat16 CUDA tensors in the layouts of include/moe_shard.h.
+    Weights are torch.bfloat16 CUDA tensors in the layouts of include/moe_shard.h.  A slice of
+    the intermediate dimension that is not a multiple of 64 is zero-padded once, here, and the
+    FFN calls then describe the padded matrices.
     ``y_perm_bf16`` / ``out_f32`` select the element types of the intermediate and the output.
     """
 
@@ -32,11 +54,16 @@ class ExpertShardLayer:
         self.E, self.k, self.H = n_experts, top_k, hidden
         self.shard = B.make_shard(n_experts, n_local_experts, expert_offset, hidden, inter_full, inter_slice)
         self.renorm = renorm
+        w_gate, w_up, w_down, padded = _pad_inter(w_gate, w_up, w_down, inter_slice)
+        self.ffn_shard = B.make_shard(n_experts, n_local_experts, expert_offset, hidden,
+                                      padded * (inter_full // inter_slice), padded)
         self.w_router, self.w_gate, self.w_up, self.w_down = w_router, w_gate, w_up, w_down
-        self.shared, self.w_shared_gate = shared, w_shared_gate
-        self.shared_shard = None
+        self.w_shared_gate = w_shared_gate
+        self.shared, self.shared_shard = None, None
         if shared is not None:
-            self.shared_shard = B.make_shard(1, 1, 0, hidden, inter_shared_full, inter_shared_slice)
+            *self.shared, padded = _pad_inter(*shared, inter_shared_slice)
+            self.shared_shard = B.make_shard(1, 1, 0, hidden, padded * (inter_shared_full // inter_shared_slice),
+                                             padded)
         self.y_perm_bf16, self.out_f32 = y_perm_bf16, out_f32
         self.device = device
         self.Tmax = -1
@@ -55,10 +82,10 @@ class ExpertShardLayer:
         self.expert_offsets = torch.empty(self.shard.n_local_experts + 1, dtype=torch.int32, device=d)
         self.row_src = torch.empty(cap, dtype=torch.int32, device=d)
         self.slot_row = torch.empty(cap, dtype=torch.int32, device=d)
-        self.h_ws = torch.empty((cap, self.shard.inter_slice), dtype=torch.bfloat16, device=d)
+        self.h_ws = torch.empty((cap, self.ffn_shard.inter_slice), dtype=torch.bfloat16, device=d)
         self.y_perm = torch.empty((cap, H), dtype=ydt, device=d)
         self.workspace = torch.empty(max(B.moe_workspace_bytes(T, k, self.shard), 256), dtype=torch.uint8, device=d)
-        self.ffn_ws = torch.empty(max(B.moe_ffn_workspace_bytes(cap, self.shard), 256), dtype=torch.uint8, device=d)
+        self.ffn_ws = torch.empty(max(B.moe_ffn_workspace_bytes(cap, self.ffn_shard), 256), dtype=torch.uint8, device=d)
         self.y_out = torch.empty((Tn, H), dtype=torch.float32 if self.out_f32 else torch.bfloat16, device=d)
         if self.shared is not None:
             self.sh_offsets = torch.zeros(2, dtype=torch.int32, device=d)
@@ -74,7 +101,7 @@ class ExpertShardLayer:
             self._alloc(T)
         k, H, E = self.k, self.H, self.E
         # the FFN scratch depends on the regime (decode-sized calls need split-K partials)
-        need = B.moe_ffn_workspace_bytes(T * k, self.shard)
+        need = B.moe_ffn_workspace_bytes(T * k, self.ffn_shard)
         if need > self.ffn_ws.numel():
             self.ffn_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
         if self.shared is not None:
@@ -89,7 +116,7 @@ class ExpertShardLayer:
         B.moe_permute(x, self.topk_idx, T, k, self.shard, self.x_perm, self.expert_offsets, self.row_src,
                       self.slot_row, self.workspace, stream=stream)
         yflag = B.MOE_Y_PERM_BF16 if self.y_perm_bf16 else 0
-        B.moe_expert_ffn(self.x_perm, self.expert_offsets, T * k, self.shard, self.w_gate, self.w_up, self.w_down,
+        B.moe_expert_ffn(self.x_perm, self.expert_offsets, T * k, self.ffn_shard, self.w_gate, self.w_up, self.w_down,
                          self.h_ws, self.y_perm, self.ffn_ws, yflag, stream)
         y_shared = None
         if self.shared is not None:

@@ -18,14 +18,25 @@ MAX_ABS = 2e-2
 N_SAMPLE = 96
 
 CASES = [("mixtral", 16), ("mixtral", 4096), ("mixtral_tp4", 64), ("mixtral_tp4", 8192),
-         ("mixtral_ep4_hot", 8192), ("mixtral_ep4_cold", 8192), ("qwen", 32), ("qwen", 4096)]
+         ("mixtral_ep4_hot", 8192), ("mixtral_ep4_cold", 8192), ("qwen", 32), ("qwen", 4096),
+         ("qwen2_57b", 32), ("qwen2_57b", 4096),
+         # hybrid shards (fewer experts AND a slice of the intermediate dimension), one per model
+         ("mixtral_tp2_ep2", 64), ("mixtral_tp2_ep2", 4096),
+         ("qwen_tp4_ep2", 32), ("qwen_tp4_ep2", 4096),      # slice 1408 / 4 = 352: zero-padded to 384
+         ("qwen2_57b_tp2_ep4", 32), ("qwen2_57b_tp2_ep4", 4096)]
+
+HYBRID = {
+    "mixtral_tp2_ep2": I.MIXTRAL.shard(tp_degree=2, tp_rank=1, ep_degree=2, ep_rank=1),
+    "qwen_tp4_ep2": I.QWEN.shard(tp_degree=4, tp_rank=1, ep_degree=2, ep_rank=0),
+    "qwen2_57b_tp2_ep4": I.QWEN2_57B.shard(tp_degree=2, tp_rank=0, ep_degree=4, ep_rank=2),
+}
 
 _cache = {}
 
 
 def _inputs(key, T):
     # weights depend on the workload only; keep one workload's weights at a time
-    shape, _ = I.WORKLOADS[key]
+    shape = HYBRID[key] if key in HYBRID else I.WORKLOADS[key][0]
     if _cache.get("key") != key:
         _cache.clear()
         _cache["key"] = key

@@ -324,6 +324,30 @@ def test_layer_hybrid_ep_tp_shard():
     assert _rel(y, ref) < REL_L2 and np.abs(y - ref).max() < MAX_ABS
 
 
+SMALL_ODD = I.MoEShape("small-odd", 256, 12, 4, 1408, False, inter_shared=704)
+
+
+@pytest.mark.parametrize("tp,T", [(4, 24), (4, 600), (8, 24), (8, 600)])
+def test_layer_tp_slices_that_are_not_a_multiple_of_64(tp, T):
+    # 1408 / 4 = 352 and 1408 / 8 = 176 (the Qwen1.5-MoE expert size under TP 4 and 8): the layer
+    # zero-pads the slice, the partial sums over all ranks still add up to the unsharded layer
+    full_li = I.make_layer_inputs(SMALL_ODD, T, 0)
+    acc = np.zeros((T, SMALL_ODD.hidden))
+    logits = None
+    for p in range(tp):
+        li = I.make_layer_inputs(SMALL_ODD.shard(tp_degree=tp, tp_rank=p), T, 0)
+        assert li.w_gate.shape[1] == 1408 // tp
+        layer, y = _run_layer(li, out_f32=True)
+        assert layer.ffn_shard.inter_slice % 64 == 0 and layer.shard.inter_slice == 1408 // tp
+        logits = _check_integers(layer, li, T)
+        ref = _oracle_layer(li, logits)
+        assert _rel(y, ref) < REL_L2 and np.abs(y - ref).max() < MAX_ABS
+        acc += y
+    # every rank adds the gated shared-expert partial sum and its own slice of the routed experts
+    ref_full = _oracle_layer(full_li, logits)
+    assert _rel(acc, ref_full) < 2 * REL_L2 and np.abs(acc - ref_full).max() < 2 * MAX_ABS
+
+
 def test_layer_is_deterministic_and_buffers_reusable():
     li = I.make_layer_inputs(SMALL_QWEN, 500, 0)
     layer = ExpertShardLayer.from_inputs(li)
