@@ -28,6 +28,8 @@ MOE_MAX_TOPK = 16
 EXPORTS = ("moe_route_topk", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_workspace_bytes",
            "moe_ffn_workspace_bytes", "moe_status_string")
 DEBUG_EXPORTS = ("moe_debug_gemm_units",)
+INT4_EXPORTS = ("moe_int4_dequantize", "moe_int4_quantize")
+INT4_GROUP = 64
 DEBUG_UNIT_INTS = 5
 
 
@@ -66,6 +68,10 @@ def lib() -> ctypes.CDLL:
         L.moe_ffn_workspace_bytes.restype = sz
         L.moe_status_string.argtypes = [ctypes.c_int]
         L.moe_status_string.restype = ctypes.c_char_p
+        L.moe_int4_dequantize.argtypes = [vp, vp, ctypes.c_int64, vp, vp]
+        L.moe_int4_dequantize.restype = ctypes.c_int
+        L.moe_int4_quantize.argtypes = [vp, ctypes.c_int64, vp, vp, vp]
+        L.moe_int4_quantize.restype = ctypes.c_int
         L.moe_debug_gemm_units.argtypes = [vp, i32, i32, i32, vp, i32]
         L.moe_debug_gemm_units.restype = i32
         _lib = L
@@ -137,6 +143,16 @@ def moe_expert_ffn(x_perm, expert_offsets, cap_rows, shard: MoeShard, w_gate, w_
 def moe_combine(y_perm, slot_row, topk_w, T, k, H, y_shared, x, w_shared_gate, y_out, flags=0, stream=None):
     _check("moe_combine", lib().moe_combine(_ptr(y_perm), _ptr(slot_row), _ptr(topk_w), T, k, H, _ptr(y_shared),
                                             _ptr(x), _ptr(w_shared_gate), _ptr(y_out), flags, _stream(stream)))
+
+
+def moe_int4_dequantize(codes, qparams, n_elems, w_bf16, stream=None):
+    _check("moe_int4_dequantize", lib().moe_int4_dequantize(_ptr(codes), _ptr(qparams), n_elems, _ptr(w_bf16),
+                                                            _stream(stream)))
+
+
+def moe_int4_quantize(w_bf16, n_elems, codes, qparams, stream=None):
+    _check("moe_int4_quantize", lib().moe_int4_quantize(_ptr(w_bf16), n_elems, _ptr(codes), _ptr(qparams),
+                                                        _stream(stream)))
 
 
 def moe_debug_gemm_units(expert_offsets, cap_rows, n_col_blocks):

@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmoe_shard.so")
-SOURCES = ["api.hip", "route.hip", "permute.hip", "expert_ffn.hip", "combine.hip", "debug_api.hip"]
+SOURCES = ["api.hip", "route.hip", "permute.hip", "expert_ffn.hip", "combine.hip", "debug_api.hip", "int4.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [*os.environ.get("MOE_EXTRA_FLAGS", "").split(), "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-I", os.path.join(ROOT, "include"),
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

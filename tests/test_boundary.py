@@ -22,7 +22,7 @@ def lib():
 def _declared_functions(header="moe_shard.h"):
     src = open(os.path.join(ROOT, "include", header)).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", src)))
+    return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", src)))
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -39,6 +39,23 @@ def test_every_declared_debug_symbol_is_exported(lib):
         assert getattr(lib, n) is not None
     src = open(os.path.join(ROOT, "include", "moe_shard_debug.h")).read()
     assert int(re.search(r"MOE_DEBUG_UNIT_INTS\s+(\d+)", src).group(1)) == B.DEBUG_UNIT_INTS
+
+
+def test_every_declared_int4_symbol_is_exported_and_validates(lib):
+    names = _declared_functions("moe_int4.h")
+    assert set(names) == set(B.INT4_EXPORTS)
+    src = open(os.path.join(ROOT, "include", "moe_int4.h")).read()
+    assert int(re.search(r"MOE_INT4_GROUP\s+(\d+)", src).group(1)) == B.INT4_GROUP
+    P = 0x1000
+    dq, q = lib.moe_int4_dequantize, lib.moe_int4_quantize
+    assert dq(P, P, 100, P, None) == B.MOE_ERR_INVALID_ARG      # not a multiple of the group size
+    assert dq(P, P, -64, P, None) == B.MOE_ERR_INVALID_ARG
+    assert dq(None, P, 64, P, None) == B.MOE_ERR_INVALID_ARG
+    assert dq(P, P, 64, P + 8, None) == B.MOE_ERR_INVALID_ARG   # misaligned
+    assert dq(P, P, 0, P, None) == B.MOE_OK                     # empty: nothing launched
+    assert q(P, 96, P, P, None) == B.MOE_ERR_INVALID_ARG
+    assert q(P, 64, None, P, None) == B.MOE_ERR_INVALID_ARG
+    assert q(P, 0, P, P, None) == B.MOE_OK
 
 
 def test_header_constants_match_binding():
