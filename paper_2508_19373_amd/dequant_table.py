@@ -13,7 +13,8 @@ import argparse
 import csv
 
 FIELDS = ["label", "v_dequant", "us", "gbs", "pct_hbm_peak"]
-BYTES_PER_WEIGHT = 0.5 + 4.0 / 64 + 2.0   # codes + (scale, min) per 64 weights read, bf16 written
+BYTES_PER_WEIGHT_IN = 0.5 + 4.0 / 64              # codes + (scale, min) per 64 weights
+BYTES_PER_WEIGHT = BYTES_PER_WEIGHT_IN + 2.0      # ... read, bf16 written
 PEAK_HBM_GBS = 8000.0
 
 
