@@ -34,6 +34,12 @@ __device__ __forceinline__ void static_for(F&& f) {
 }
 
 // largest divisor of n in [6, 12], else the largest one below 6
+// largest divisor of n that is at most cap
+constexpr int ring_cap(int n, int cap) {
+  for (int r = cap; r >= 1; --r)
+    if (n % r == 0) return r;
+  return 1;
+}
 constexpr int ring_size(int n) {
   for (int r = 12; r >= 6; --r)
     if (n % r == 0) return r;
@@ -52,7 +58,10 @@ __global__ __launch_bounds__(NW * 64, (MT == 1 ? 4 : 2)) void grouped_walk_kerne
     const uint16_t* __restrict__ Wb, int n_out, int K, void* __restrict__ Cv, int strips_per_wg, int cap_rows) {
   constexpr int NB = GATEUP ? 2 : 1;
   constexpr int ITEMS = NB * STEPS;  // weight loads (1 KB each) per strip per wave
-  constexpr int RING = ring_size(ITEMS);
+  // MT = 1 has 128 VGPRs: 4 * STEPS hold the activations, and a ring that does not fit next to them
+  // spills (8 slots beside 16 steps: 60 bytes of scratch per lane and 4 % of the HBM rate)
+  constexpr int RING = (MT == 1 && 4 * STEPS + 4 * ring_size(ITEMS) > 92) ? ring_cap(ITEMS, (92 - 4 * STEPS) / 4)
+                                                                          : ring_size(ITEMS);
   constexpr int TILES = NB * MT;
   __shared__ float red[2][NW][TILES][256];
 
