@@ -8,8 +8,10 @@
 //
 // Design for CDNA4:
 //  * one workgroup per (expert, row block, column block) tile, 4 wavefronts of 128 x 128 outputs;
-//  * operands go global -> LDS directly (global_load_lds_dwordx4, no VGPR staging), two LDS
-//    stages of BM x 64 + BN x 64 bf16;
+//  * operands go global -> LDS directly (global_load_lds_dwordx4, no VGPR staging) into all
+//    160 KB of LDS: 2 activation + 3 weight stages of a 64-wide k-tile for a 256-row tile, 3 + 3 and
+//    4 + 4 stages for the 128- and 64-row remainder tiles (an HBM round trip under load is longer
+//    than one k-tile of MFMA work);
 //  * LDS rows are 128 bytes; the 16-byte chunk index is XOR-swizzled with (row/2)%8, applied
 //    on the global side of the DMA (a lane fetches the chunk that belongs at its LDS slot),
 //    so operand reads (ds_read_b128) are bank-conflict free;
@@ -82,8 +84,8 @@ constexpr int dma_slack(int j, int NSA, int NSB, int A_INST, int B_INST) {
 // half the accumulator bytes per FLOP).  Pairing needs both k32 halves of a 64-wide k-tile for
 // the same accumulator, so the operands of the WHOLE k-tile live in registers (2*(TM+TN)
 // fragments) and are refreshed in place: a fragment is re-read from the next k-tile's LDS stage
-// right after its last use.  LDS is then a two-stage landing buffer in front of the register
-// tile (a three-deep pipeline), still with one barrier per k-tile.
+// right after its last use.  LDS is then a multi-stage landing buffer in front of the register
+// tile, still with one barrier per k-tile.
 // The traversal order and the refresh schedule are described at k_tile below.
 template <int BM, int BN, int WM, int WN, int NSA, int NSB, bool GATEUP, typename OutT>
 __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, const uint16_t* __restrict__ A,

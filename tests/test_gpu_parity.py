@@ -162,6 +162,10 @@ def _ffn_gpu(x_perm_bits, offs, shard, wg, wu, wd, y_bf16=False):
     (2048, 5632, [12]),                              # shared-expert shape at decode, 2 K slices
     (512, 1024, [16, 2, 0, 9]),                      # decode: generic streaming (H) + 4x8 split (I)
     (512, 1024, [40, 30, 7]),                        # decode regime with more than 32 rows in one expert
+    (64, 64, [300, 129, 40]),                        # prefill kernel with a single k-tile (shorter than its pipeline)
+    (128, 192, [257, 40, 100]),                      # two and three k-tiles: every tail path of the DMA pipeline
+    (192, 128, [100, 500, 64]),
+    (256, 320, [64, 128, 21, 256]),                  # four and five k-tiles, all three tile heights
 ])
 def test_expert_ffn_against_oracle(H, I_s, counts):
     n = len(counts)
