@@ -47,7 +47,8 @@ def _route_gpu(x_bits, w_router, logits, T, H, E, k, renorm):
 # ------------------------------------------------------------------ route
 @pytest.mark.parametrize("shape,T", [(I.TINY, 64), (I.MoEShape("q", 256, 60, 4, 128, False), 77),
                                      (I.MoEShape("wide", 128, 200, 6, 128, True), 33),
-                                     (I.MoEShape("odd", 64, 13, 3, 128, True), 5)])
+                                     (I.MoEShape("odd", 64, 13, 3, 128, True), 5),
+                                     (I.MoEShape("max", 192, 256, 16, 128, False), 40)])   # E and k at their limits
 def test_route_logits_and_topk(shape, T):
     li = I.make_layer_inputs(shape, T, 0, weights=False)
     E, k = shape.n_experts, shape.top_k
@@ -104,7 +105,8 @@ def _permute_gpu(x_bits, idx, shard):
 
 @pytest.mark.parametrize("T,k,E,n_local,off", [
     (64, 2, 8, 8, 0), (1500, 2, 8, 8, 0), (1500, 2, 8, 2, 6), (4096, 4, 60, 60, 0), (777, 4, 60, 15, 30),
-    (1, 1, 8, 8, 0), (513, 3, 200, 200, 0), (8192, 2, 8, 2, 0), (0, 2, 8, 8, 0), (16, 2, 8, 1, 7)])
+    (1, 1, 8, 8, 0), (513, 3, 200, 200, 0), (8192, 2, 8, 2, 0), (0, 2, 8, 8, 0), (16, 2, 8, 1, 7),
+    (300, 16, 256, 256, 0), (300, 16, 256, 64, 128)])   # E = 256 and k = 16: the limits of the implementation
 def test_permute_bit_exact(T, k, E, n_local, off):
     rng = np.random.default_rng(T + k + E)
     H = 64
@@ -350,6 +352,15 @@ def test_layer_tp_slices_that_are_not_a_multiple_of_64(tp, T):
     # every rank adds the gated shared-expert partial sum and its own slice of the routed experts
     ref_full = _oracle_layer(full_li, logits)
     assert _rel(acc, ref_full) < 2 * REL_L2 and np.abs(acc - ref_full).max() < 2 * MAX_ABS
+
+
+def test_layer_at_the_expert_and_topk_limits():
+    s = I.MoEShape("limits", 128, 256, 16, 64, True)
+    for T in (7, 130):
+        li = I.make_layer_inputs(s, T, 0)
+        layer, y = _run_layer(li, out_f32=True)
+        ref = _oracle_layer(li, _check_integers(layer, li, T))
+        assert _rel(y, ref) < REL_L2 and np.abs(y - ref).max() < MAX_ABS
 
 
 def test_layer_is_deterministic_and_buffers_reusable():
