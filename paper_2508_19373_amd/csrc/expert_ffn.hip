@@ -51,14 +51,15 @@ hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, i
 
 // Decode-sized groups, register-resident activations (grouped_walk.hpp).  Returns false when the
 // K extent is not one of the instantiated (wavefronts x steps) splits.
-constexpr int kWalkSlots = 512;  // workgroups resident at once with MT = 1 (2 per CU; 1 per CU with MT = 2)
+constexpr int kWalkSlots = 512;  // 8-wavefront workgroups resident at once with MT = 1 (2 per CU); half of it
+                                  // with MT = 2 or 16 wavefronts (1 per CU)
 
 template <int MT, bool GATEUP>
 bool launch_walk(const gw::WalkPlan& plan, const uint16_t* A, const int32_t* expert_offsets, int n_local,
                  const uint16_t* Wa, const uint16_t* Wb, int n_out, int K, void* C, int cap_rows,
                  hipStream_t stream) {
   const int total_strips = n_out / 16;
-  int chunks = (MT == 1 ? kWalkSlots : kWalkSlots / 2) / (n_local * plan.slices);
+  int chunks = (MT == 1 && plan.nw < 16 ? kWalkSlots : kWalkSlots / 2) / (n_local * plan.slices);
   chunks = chunks < 1 ? 1 : (chunks > total_strips ? total_strips : chunks);
   const int spw = (total_strips + chunks - 1) / chunks;
   const dim3 grid((total_strips + spw - 1) / spw, n_local, plan.slices);
@@ -67,6 +68,14 @@ bool launch_walk(const gw::WalkPlan& plan, const uint16_t* A, const int32_t* exp
     hipLaunchKernelGGL((gw::grouped_walk_kernel<NW, ST, MT, GATEUP>), grid, dim3(NW * 64), 0, stream, A,        \
                        expert_offsets, Wa, Wb, n_out, K, C, spw, cap_rows);                                     \
     return true;                                                                                                \
+  }
+  if constexpr (MT == 1) {
+    MOE_WALK(16, 14)
+    MOE_WALK(16, 11)
+    MOE_WALK(16, 8)
+    MOE_WALK(16, 7)
+    MOE_WALK(16, 5)
+    MOE_WALK(16, 4)
   }
   MOE_WALK(8, 16)
   MOE_WALK(8, 14)
@@ -92,7 +101,7 @@ hipError_t launch_pair_decode(const void* x_perm, const int32_t* expert_offsets,
   uint16_t* hw = static_cast<uint16_t*>(h_ws);
   if (n_local > 65535) return hipErrorInvalidValue;
   if (!(flags & MOE_FFN_SKIP_GATEUP)) {
-    const gw::WalkPlan p1 = gw::plan_for(H);
+    const gw::WalkPlan p1 = gw::plan_for(H, MT);
     bool done = false;
     if (p1.nw != 0 && p1.slices == 1 && I_s % 16 == 0)
       done = launch_walk<MT, true>(p1, xp, expert_offsets, n_local, static_cast<const uint16_t*>(w_gate),
@@ -107,7 +116,7 @@ hipError_t launch_pair_decode(const void* x_perm, const int32_t* expert_offsets,
     if (err != hipSuccess) return err;
   }
   if (flags & MOE_FFN_SKIP_DOWN) return hipSuccess;
-  const gw::WalkPlan p2 = gw::plan_for(I_s);
+  const gw::WalkPlan p2 = gw::plan_for(I_s, MT);
   if (!y_bf16 && p2.nw != 0 && H % 16 == 0 && (p2.slices == 1 || workspace != nullptr)) {
     void* out = p2.slices == 1 ? y_perm : workspace;
     if (launch_walk<MT, false>(p2, hw, expert_offsets, n_local, static_cast<const uint16_t*>(w_down),
@@ -132,12 +141,16 @@ hipError_t launch_pair_decode(const void* x_perm, const int32_t* expert_offsets,
 }
 
 inline bool decode_regime(int cap_rows, int n_local) { return cap_rows / n_local <= 20; }
+// MT = 1 (16 activation rows per pass) when experts hold about 8 rows or fewer on average: it keeps
+// twice the bytes in flight, and the rare expert with more than 16 rows only pays a second pass
+// over its own weights.
+inline int decode_mt(int cap_rows, int n_local) { return (cap_rows <= 16 || cap_rows / n_local <= 8) ? 1 : 2; }
 
 }  // namespace
 
 size_t ffn_workspace_bytes(int cap_rows, int n_local, int H, int I_s) {
   if (cap_rows == 0 || !decode_regime(cap_rows, n_local)) return 0;
-  const gw::WalkPlan p2 = gw::plan_for(I_s);
+  const gw::WalkPlan p2 = gw::plan_for(I_s, decode_mt(cap_rows, n_local));
   if (p2.nw == 0 || p2.slices == 1) return 0;
   return (size_t)p2.slices * cap_rows * H * sizeof(float);
 }
@@ -151,10 +164,7 @@ hipError_t launch_expert_ffn(const void* x_perm, const int32_t* expert_offsets, 
   // The average capacity per local expert picks the regime: a few rows per expert are bound by
   // streaming the weights once (decode), many rows by the matrix cores (prefill).
   if (decode_regime(cap_rows, n_local)) {
-    // MT = 1 (16 activation rows per pass) when experts hold about 8 rows or fewer on average:
-    // it keeps twice the wavefronts in flight, and the rare expert with more than 16 rows only
-    // pays a second pass over its own weights.
-    if (cap_rows <= 16 || cap_rows / n_local <= 8)
+    if (decode_mt(cap_rows, n_local) == 1)
       return launch_pair_decode<1>(x_perm, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,
                                    y_perm, workspace, flags, stream);
     return launch_pair_decode<2>(x_perm, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,

@@ -184,9 +184,18 @@ __global__ __launch_bounds__(256) void sum_slices_kernel(const float* __restrict
 struct WalkPlan {
   int nw, steps, slices;  // nw == 0: shape not covered, use the generic streaming kernel
 };
-inline WalkPlan plan_for(int K) {
+// mt = 1 (at most 16 rows per pass, 128 VGPRs per lane): sixteen wavefronts per workgroup with at
+// most 14 k32 steps each leave room for a weight ring as long as a strip, twice the bytes in flight
+// per compute unit of the 8-wavefront split (measured 6.2 against 5.9 TB/s).  mt = 2 holds twice
+// the activation registers and stays with 8 or 4 wavefronts at 256 VGPRs.
+inline WalkPlan plan_for(int K, int mt) {
   const int steps32 = K / 32;
   if (K % 32 == 0) {
+    if (mt == 1) {
+      const int cand16[6] = {14, 11, 8, 7, 5, 4};  // instantiated with 16 wavefronts
+      for (int st : cand16)
+        if (steps32 % (16 * st) == 0) return WalkPlan{16, st, steps32 / (16 * st)};
+    }
     const int nws[2] = {8, 4};
     const int cand[7] = {16, 14, 11, 10, 8, 7, 5};
     for (int nw : nws)

@@ -140,7 +140,7 @@ def test_expert_ffn_validation(lib):
     # decode-sized call on a Mixtral-shaped shard needs split-K scratch; a prefill-sized one does not
     mix = _shard(hidden=4096, inter_full=14336, inter_slice=14336)
     need = B.moe_ffn_workspace_bytes(32, mix)
-    assert need == 4 * 32 * 4096 * 4
+    assert need == 2 * 32 * 4096 * 4   # 16 wavefronts x 14 k-steps x 2 K slices
     assert B.moe_ffn_workspace_bytes(8192, mix) == 0
     assert f(P, P, 32, ctypes.byref(mix), P, P, P, P, P, None, 0, 0, None) == B.MOE_ERR_WORKSPACE
     assert f(P, P, 32, ctypes.byref(mix), P, P, P, P, P, P, need - 1, 0, None) == B.MOE_ERR_WORKSPACE
