@@ -60,8 +60,11 @@ __global__ __launch_bounds__(NW * 64, (MT == 1 ? 4 : 2)) void grouped_walk_kerne
   constexpr int ITEMS = NB * STEPS;  // weight loads (1 KB each) per strip per wave
   // MT = 1 has 128 VGPRs: 4 * STEPS hold the activations, and a ring that does not fit next to them
   // spills (8 slots beside 16 steps: 60 bytes of scratch per lane and 4 % of the HBM rate)
-  constexpr int RING = (MT == 1 && 4 * STEPS + 4 * ring_size(ITEMS) > 92) ? ring_cap(ITEMS, (92 - 4 * STEPS) / 4)
-                                                                          : ring_size(ITEMS);
+  // MT = 2 has 256 VGPRs and half the wavefronts per CU: a ring of up to 16 slots restores the
+  // bytes in flight.
+  constexpr int RING = MT == 2 ? ring_cap(ITEMS, (216 - 8 * STEPS) / 4 < 16 ? (216 - 8 * STEPS) / 4 : 16)
+                               : ((4 * STEPS + 4 * ring_size(ITEMS) > 92) ? ring_cap(ITEMS, (92 - 4 * STEPS) / 4)
+                                                                           : ring_size(ITEMS));
   constexpr int TILES = NB * MT;
   __shared__ float red[2][NW][TILES][256];
 
