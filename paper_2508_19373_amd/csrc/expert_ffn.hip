@@ -15,6 +15,8 @@
 #include "grouped_walk.hpp"
 #include "moe_internal.hpp"
 
+#include <cmath>
+
 namespace moe {
 namespace {
 
@@ -140,16 +142,37 @@ hipError_t launch_pair_decode(const void* x_perm, const int32_t* expert_offsets,
   return hipGetLastError();
 }
 
-inline bool decode_regime(int cap_rows, int n_local) { return cap_rows / n_local <= 20; }
 // MT = 1 (16 activation rows per pass) when experts hold about 8 rows or fewer on average: it keeps
 // twice the bytes in flight, and the rare expert with more than 16 rows only pays a second pass
 // over its own weights.
 inline int decode_mt(int cap_rows, int n_local) { return (cap_rows <= 16 || cap_rows / n_local <= 8) ? 1 : 2; }
 
+// Which kernel family runs one of the two GEMMs: the weight-streaming walk (decode regime) or the
+// tiled LDS-DMA kernel (prefill regime).  A few rows per expert are bound by streaming the
+// weights once, many rows by the matrix cores; in between, what decides is how often the walk has
+// to re-stream an expert (one pass per 16 or 32 rows) against how many tiles the tiled kernel can
+// spread over the compute units (a tile streams its weight panel at about 40 GB/s, so a down
+// projection of a single shared expert -- H / 256 = 14 tiles -- would use 14 CUs).  Estimates in
+// seconds from measured rates: walk 5.5 TB/s, tiled kernel min(5 TB/s, 40 GB/s per tile) and
+// 1.2 PFLOP/s.  Routed experts get a two-sigma margin on the rows of the fullest expert.
+inline bool prefer_walk(int cap_rows, int n_local, int n_out, int K, bool gateup) {
+  const double mats = gateup ? 2.0 : 1.0;
+  const double avg = (double)cap_rows / n_local;
+  const double rows_hi = n_local == 1 ? avg : avg + 2.0 * sqrt(avg);
+  const double passes = ceil(rows_hi / (decode_mt(cap_rows, n_local) == 1 ? 16.0 : 32.0));
+  const double bytes = mats * n_local * (double)n_out * K * 2.0;
+  const double walk = passes * bytes / 5.5e12;
+  const int ncols = gateup ? 128 : 256;
+  const double tiles = (double)(cap_rows / 256 + n_local) * ((n_out + ncols - 1) / ncols);
+  const double stream = bytes / fmin(5.0e12, tiles * 40e9);
+  const double mfma = 2.0 * mats * cap_rows * (double)n_out * K / 1.2e15;
+  return walk < fmax(stream, mfma);
+}
+
 }  // namespace
 
 size_t ffn_workspace_bytes(int cap_rows, int n_local, int H, int I_s) {
-  if (cap_rows == 0 || !decode_regime(cap_rows, n_local)) return 0;
+  if (cap_rows == 0 || !prefer_walk(cap_rows, n_local, H, I_s, false)) return 0;
   const gw::WalkPlan p2 = gw::plan_for(I_s, decode_mt(cap_rows, n_local));
   if (p2.nw == 0 || p2.slices == 1) return 0;
   return (size_t)p2.slices * cap_rows * H * sizeof(float);
@@ -161,17 +184,24 @@ hipError_t launch_expert_ffn(const void* x_perm, const int32_t* expert_offsets, 
                              hipStream_t stream) {
   (void)workspace_bytes;
   if (cap_rows == 0) return hipSuccess;
-  // The average capacity per local expert picks the regime: a few rows per expert are bound by
-  // streaming the weights once (decode), many rows by the matrix cores (prefill).
-  if (decode_regime(cap_rows, n_local)) {
-    if (decode_mt(cap_rows, n_local) == 1)
+  // each GEMM picks its kernel family on its own: h is row-major bf16 for both
+  const int mt = decode_mt(cap_rows, n_local);
+  auto run = [&](bool walk, uint32_t f) {
+    if (!walk)
+      return launch_pair_dlds<256>(x_perm, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,
+                                   y_perm, f, stream);
+    if (mt == 1)
       return launch_pair_decode<1>(x_perm, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,
-                                   y_perm, workspace, flags, stream);
+                                   y_perm, workspace, f, stream);
     return launch_pair_decode<2>(x_perm, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,
-                                 y_perm, workspace, flags, stream);
-  }
-  return launch_pair_dlds<256>(x_perm, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,
-                               y_perm, flags, stream);
+                                 y_perm, workspace, f, stream);
+  };
+  const bool walk1 = prefer_walk(cap_rows, n_local, I_s, H, true), walk2 = prefer_walk(cap_rows, n_local, H, I_s, false);
+  if (walk1 == walk2 || (flags & (MOE_FFN_SKIP_GATEUP | MOE_FFN_SKIP_DOWN)))
+    return run((flags & MOE_FFN_SKIP_GATEUP) ? walk2 : walk1, flags);
+  const hipError_t err = run(walk1, flags | MOE_FFN_SKIP_DOWN);
+  if (err != hipSuccess) return err;
+  return run(walk2, flags | MOE_FFN_SKIP_GATEUP);
 }
 
 }  // namespace moe
