@@ -119,7 +119,7 @@ int moe_permute(const void* x_bf16, const int32_t* topk_idx, int32_t T, int32_t 
  * w_down         [E_loc][H][I_s] bf16   (row = output feature, I_s contiguous)
  * h_workspace    [cap_rows,I_s] bf16    the activated intermediate h (output of GEMM1)
  * workspace      at least moe_ffn_workspace_bytes(cap_rows, shard) bytes, 256-byte aligned
- *                (split-K partial sums of the decode path); may be NULL when that is 0
+ *                (fp32 partial sums of launches that are cut along K); may be NULL when that is 0
  * y_perm         [cap_rows,H] fp32 (bf16 with MOE_Y_PERM_BF16); rows [0,R) written
  * With inter_slice < inter_full, y_perm is the tensor-parallel partial sum.
  * The shared expert is a second call with n_local_experts = 1, expert_offsets = {0,T},

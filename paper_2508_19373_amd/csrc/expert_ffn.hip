@@ -24,7 +24,7 @@ namespace {
 template <int BN>
 hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, int cap_rows, int n_local, int H,
                             int I_s, const void* w_gate, const void* w_up, const void* w_down, void* h_ws,
-                            void* y_perm, uint32_t flags, hipStream_t stream) {
+                            void* y_perm, void* workspace, uint32_t flags, hipStream_t stream) {
   const bool y_bf16 = (flags & MOE_Y_PERM_BF16) != 0;
   const dim3 block(256);
   const uint16_t* xp = static_cast<const uint16_t*>(x_perm);
@@ -40,14 +40,22 @@ hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, i
   }
   if (flags & MOE_FFN_SKIP_DOWN) return hipSuccess;
   const int ncb = (H + BN - 1) / BN;
-  if (y_bf16)
+  const int slices = (y_bf16 || workspace == nullptr) ? 1 : gg::k_slices_for(cap_rows, n_local, ncb, I_s);
+  if (y_bf16) {
     hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, uint16_t>), grid_for(ncb), block, 0, stream, hw,
                        expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_down),
                        static_cast<const uint16_t*>(nullptr), H, I_s, static_cast<uint16_t*>(y_perm), ncb);
-  else
-    hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, float>), grid_for(ncb), block, 0, stream, hw,
-                       expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_down),
-                       static_cast<const uint16_t*>(nullptr), H, I_s, static_cast<float*>(y_perm), ncb);
+    return hipGetLastError();
+  }
+  dim3 grid = grid_for(ncb);
+  grid.y = slices;
+  hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, float>), grid, block, 0, stream, hw, expert_offsets,
+                     n_local, cap_rows, static_cast<const uint16_t*>(w_down), static_cast<const uint16_t*>(nullptr),
+                     H, I_s, static_cast<float*>(slices > 1 ? workspace : y_perm), ncb);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess || slices == 1) return err;
+  hipLaunchKernelGGL(gw::sum_slices_kernel, dim3(256), dim3(256), 0, stream, static_cast<const float*>(workspace),
+                     expert_offsets, n_local, cap_rows, H, slices, static_cast<float*>(y_perm));
   return hipGetLastError();
 }
 
@@ -152,18 +160,18 @@ inline int decode_mt(int cap_rows, int n_local) { return (cap_rows <= 16 || cap_
 // weights once, many rows by the matrix cores; in between, what decides is how often the walk has
 // to re-stream an expert (one pass per 16 or 32 rows) against how many tiles the tiled kernel can
 // spread over the compute units (a tile streams its weight panel at about 40 GB/s, so a down
-// projection of a single shared expert -- H / 256 = 14 tiles -- would use 14 CUs).  Estimates in
-// seconds from measured rates: walk 5.5 TB/s, tiled kernel min(5 TB/s, 40 GB/s per tile) and
-// 1.2 PFLOP/s.  Routed experts get a two-sigma margin on the rows of the fullest expert.
+// projection of a single shared expert -- H / 256 = 14 tiles -- would use 14 CUs, which is why such
+// a launch is also cut along K).  Estimates in seconds from measured rates: walk 5.5 TB/s plus 5 us
+// per pass, tiled kernel min(5 TB/s, 40 GB/s per tile and K slice) and 1.2 PFLOP/s.  Routed experts get a two-sigma margin on the rows of the fullest expert.
 inline bool prefer_walk(int cap_rows, int n_local, int n_out, int K, bool gateup) {
   const double mats = gateup ? 2.0 : 1.0;
   const double avg = (double)cap_rows / n_local;
   const double rows_hi = n_local == 1 ? avg : avg + 2.0 * sqrt(avg);
   const double passes = ceil(rows_hi / (decode_mt(cap_rows, n_local) == 1 ? 16.0 : 32.0));
   const double bytes = mats * n_local * (double)n_out * K * 2.0;
-  const double walk = passes * bytes / 5.5e12;
-  const int ncols = gateup ? 128 : 256;
-  const double tiles = (double)(cap_rows / 256 + n_local) * ((n_out + ncols - 1) / ncols);
+  const double walk = passes * (bytes / 5.5e12 + 5e-6);  // a pass also pays its ramp-up
+  const int ncb = (n_out + (gateup ? 127 : 255)) / (gateup ? 128 : 256);
+  const double tiles = (double)(cap_rows / 256 + n_local) * ncb * (gateup ? 1 : gg::k_slices_for(cap_rows, n_local, ncb, K));
   const double stream = bytes / fmin(5.0e12, tiles * 40e9);
   const double mfma = 2.0 * mats * cap_rows * (double)n_out * K / 1.2e15;
   return walk < fmax(stream, mfma);
@@ -172,10 +180,15 @@ inline bool prefer_walk(int cap_rows, int n_local, int n_out, int K, bool gateup
 }  // namespace
 
 size_t ffn_workspace_bytes(int cap_rows, int n_local, int H, int I_s) {
-  if (cap_rows == 0 || !prefer_walk(cap_rows, n_local, H, I_s, false)) return 0;
-  const gw::WalkPlan p2 = gw::plan_for(I_s, decode_mt(cap_rows, n_local));
-  if (p2.nw == 0 || p2.slices == 1) return 0;
-  return (size_t)p2.slices * cap_rows * H * sizeof(float);
+  if (cap_rows == 0) return 0;
+  int slices;
+  if (prefer_walk(cap_rows, n_local, H, I_s, false)) {
+    const gw::WalkPlan p2 = gw::plan_for(I_s, decode_mt(cap_rows, n_local));
+    slices = p2.nw == 0 ? 1 : p2.slices;
+  } else {
+    slices = gg::k_slices_for(cap_rows, n_local, (H + 255) / 256, I_s);
+  }
+  return slices > 1 ? (size_t)slices * cap_rows * H * sizeof(float) : 0;
 }
 
 hipError_t launch_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int cap_rows, int n_local, int H,
@@ -189,7 +202,7 @@ hipError_t launch_expert_ffn(const void* x_perm, const int32_t* expert_offsets, 
   auto run = [&](bool walk, uint32_t f) {
     if (!walk)
       return launch_pair_dlds<256>(x_perm, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,
-                                   y_perm, f, stream);
+                                   y_perm, workspace, f, stream);
     if (mt == 1)
       return launch_pair_decode<1>(x_perm, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,
                                    y_perm, workspace, f, stream);

@@ -90,7 +90,7 @@ constexpr int dma_slack(int j, int NSA, int NSB, int A_INST, int B_INST) {
 template <int BM, int BN, int WM, int WN, int NSA, int NSB, bool GATEUP, typename OutT>
 __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, const uint16_t* __restrict__ A,
                                             int cap_rows, const uint16_t* __restrict__ B0,
-                                            const uint16_t* __restrict__ B1, int n_out, int K,
+                                            const uint16_t* __restrict__ B1, int n_out, int K, int kt0, int nk,
                                             OutT* __restrict__ C) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 16, TN = BN / WN / 16;
@@ -118,7 +118,7 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
     const int r = inst * 8 + (lane >> 3);
     const int c = (lane & 7) ^ swz(r);
     const int gr = min(row0 + r, cap_rows - 1);
-    a_src[j] = A + (size_t)gr * K + c * 8;
+    a_src[j] = A + (size_t)gr * K + (size_t)kt0 * BK + c * 8;
   }
   const size_t expert_stride = (size_t)n_out * K;
 #pragma unroll
@@ -136,7 +136,7 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
       wrow = col0 + r;
     }
     wrow = min(wrow, n_out - 1);
-    b_src[j] = base + (size_t)tc.expert * expert_stride + (size_t)wrow * K + c * 8;
+    b_src[j] = base + (size_t)tc.expert * expert_stride + (size_t)wrow * K + (size_t)kt0 * BK + c * 8;
   }
 
   constexpr int N_DMA = A_INST + B_INST;
@@ -175,7 +175,6 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
 #pragma unroll
     for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  const int nk = K / BK;
   using T_ = std::true_type;
   using F_ = std::false_type;
   template_int<0> k0_;
@@ -326,7 +325,10 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
 }
 
 // Kernel: 256 threads (4 wavefronts); each workgroup computes one tile, whose height class
-// selects the wave arrangement and the LDS stage counts.
+// selects the wave arrangement and the LDS stage counts.  grid.y = K slices: slice z covers k-tiles
+// [z, z+1) * K / 64 / gridDim.y and writes its partial sums to C + z * cap_rows * n_out (a launch
+// whose tiles would fill less than half the compute units is cut along K; the caller adds the
+// slices in order).
 template <int BN, bool GATEUP, typename OutT>
 __global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
     const uint16_t* __restrict__ A, const int32_t* __restrict__ expert_offsets, int n_local, int cap_rows,
@@ -336,12 +338,24 @@ __global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
   const Unit u = find_unit(count_tiles(expert_offsets, n_local, n_col_blocks), blockIdx.x);
   if (u.cls < 0) return;
   const TileCoord tc = locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx);
+  const int nk = K / BK / gridDim.y, kt0 = blockIdx.y * nk;
+  OutT* out = C + (size_t)blockIdx.y * cap_rows * n_out;
   if (u.cls == 0)
-    gemm_tile<256, BN, 2, 2, 2, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, C);
+    gemm_tile<256, BN, 2, 2, 2, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out);
   else if (u.cls == 1)
-    gemm_tile<128, BN, 2, 2, 3, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, C);
+    gemm_tile<128, BN, 2, 2, 3, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out);
   else
-    gemm_tile<64, BN, 1, 4, 4, 4, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, C);
+    gemm_tile<64, BN, 1, 4, 4, 4, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out);
+}
+
+// K slices for a down projection whose tile count would leave most compute units idle (a single
+// shared expert with a few hundred rows: H / 256 column blocks per row block): the largest of 8, 4,
+// 2 that divides the k-tile count, keeps at least 8 k-tiles per slice and at most 256 workgroups.
+inline int k_slices_for(int cap_rows, int n_local, int n_col_blocks, int K) {
+  const int tiles = (cap_rows / 256 + n_local) * n_col_blocks, nk = K / BK;
+  for (int s = 8; s >= 2; s >>= 1)
+    if (tiles * s <= 256 && nk % s == 0 && nk / s >= 8) return s;
+  return 1;
 }
 
 }  // namespace gg

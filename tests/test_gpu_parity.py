@@ -168,6 +168,8 @@ def _ffn_gpu(x_perm_bits, offs, shard, wg, wu, wd, y_bf16=False):
     (128, 192, [257, 40, 100]),                      # two and three k-tiles: every tail path of the DMA pipeline
     (192, 128, [100, 500, 64]),
     (256, 320, [64, 128, 21, 256]),                  # four and five k-tiles, all three tile heights
+    (512, 4096, [2000]),                             # one expert, few column blocks, long K: down projection in 8 K slices
+    (256, 2048, [700, 0, 900]),                      # ... in 4 K slices, with remainder tiles and an empty expert
 ])
 def test_expert_ffn_against_oracle(H, I_s, counts):
     n = len(counts)
