@@ -135,7 +135,10 @@ __global__ __launch_bounds__(kRouteThreads) void route_topk_kernel(
 // x[t0+m, c*32 + kq*8 + s] and the B lane (n, kq) the matching W_r row.
 constexpr int kLogitTok = 16;
 
-template <int NT, int NWV, int UNR>  // 16-expert column tiles, wavefronts, chunks in flight per wavefront
+// SELECT = false (decode-sized batches with more than 16 experts): grid.y walks the 16-expert
+// column tiles, one per workgroup, so that a batch of 32 tokens is spread over 2 x E/16 workgroups
+// instead of 2; the logits go to global memory and route_topk_kernel selects from there.
+template <int NT, int NWV, int UNR, bool SELECT>  // 16-expert column tiles, wavefronts, chunks in flight per wavefront
 __global__ __launch_bounds__(NWV * 64) void router_logits_kernel(const uint16_t* __restrict__ x,
                                                                  const float* __restrict__ w_router,
                                                                  float* __restrict__ logits, int T, int H, int E,
@@ -146,6 +149,7 @@ __global__ __launch_bounds__(NWV * 64) void router_logits_kernel(const uint16_t*
   __shared__ float tile[16][NT * 16 + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int t0 = blockIdx.x * kLogitTok;
+  const int e_base = SELECT ? 0 : blockIdx.y * (NT * 16);
   const int m = lane & 15, kq = lane >> 4;
   const int trow = min(t0 + m, T - 1);
   const uint16_t* xr = x + (size_t)trow * H + kq * 8;
@@ -161,11 +165,11 @@ __global__ __launch_bounds__(NWV * 64) void router_logits_kernel(const uint16_t*
       const int c = min(c0 + u * NWV, n_chunks - 1);  // past the end: re-read, weight forced to 0 below
       const bool live = c0 + u * NWV < n_chunks;
       xv[u] = *reinterpret_cast<const uint4*>(xr + c * 32);
-      const float* wr = w_router + (size_t)(c * 32 + kq * 8) * E + m;
+      const float* wr = w_router + (size_t)(c * 32 + kq * 8) * E + e_base + m;
 #pragma unroll
       for (int s = 0; s < 8; ++s)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) wv[u][s][nt] = (live && nt * 16 + m < E) ? wr[(size_t)s * E + nt * 16] : 0.f;
+        for (int nt = 0; nt < NT; ++nt) wv[u][s][nt] = (live && e_base + nt * 16 + m < E) ? wr[(size_t)s * E + nt * 16] : 0.f;
     }
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
@@ -184,13 +188,14 @@ __global__ __launch_bounds__(NWV * 64) void router_logits_kernel(const uint16_t*
   __syncthreads();
   for (int idx = tid; idx < NT * 256; idx += NWV * 64) {
     const int nt = idx >> 8, row = (idx >> 4) & 15, col = idx & 15;
-    const int e = nt * 16 + col, t = t0 + row;
+    const int e = e_base + nt * 16 + col, t = t0 + row;
     float sum = 0.f;
 #pragma unroll
     for (int w = 0; w < NWV; ++w) sum += part[w][nt][row][col];
     tile[row][nt * 16 + col] = sum;
     if (e < E && t < T) logits[(size_t)t * E + e] = sum;
   }
+  if constexpr (!SELECT) return;
   __syncthreads();
   // selection: one wavefront per token, straight from the logits tile in LDS
   constexpr int EPL = (NT * 16 + kWave - 1) / kWave;
@@ -210,8 +215,8 @@ __global__ __launch_bounds__(NWV * 64) void router_logits_kernel(const uint16_t*
 template <int NT, int NWV, int UNR>
 void launch_logits(const uint16_t* x, const float* w_router, float* logits, int T, int H, int E, int k, uint32_t flags,
                    int32_t* topk_idx, float* topk_w, hipStream_t stream) {
-  hipLaunchKernelGGL((router_logits_kernel<NT, NWV, UNR>), dim3((T + kLogitTok - 1) / kLogitTok), dim3(NWV * 64), 0,
-                     stream, x, w_router, logits, T, H, E, k, flags, topk_idx, topk_w);
+  hipLaunchKernelGGL((router_logits_kernel<NT, NWV, UNR, true>), dim3((T + kLogitTok - 1) / kLogitTok),
+                     dim3(NWV * 64), 0, stream, x, w_router, logits, T, H, E, k, flags, topk_idx, topk_w);
 }
 
 }  // namespace
@@ -222,14 +227,20 @@ hipError_t launch_route_topk(const void* x, const float* w_router, float* logits
   const dim3 grid((T + kTokPerBlock - 1) / kTokPerBlock), block(kRouteThreads);
   const uint16_t* xs = static_cast<const uint16_t*>(x);
   if (!(flags & MOE_LOGITS_GIVEN) && H % 32 == 0) {
-    // logits by MFMA and the selection from the logits tile, in one kernel
     const int nt = (E + 15) / 16;
-    if (nt <= 1) launch_logits<1, 16, 4>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
-    else if (nt <= 2) launch_logits<2, 16, 4>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
-    else if (nt <= 4) launch_logits<4, 16, 2>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
-    else if (nt <= 8) launch_logits<8, 8, 1>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
-    else launch_logits<16, 4, 1>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
-    return hipGetLastError();
+    if (nt < 2 || T > 128) {  // logits by MFMA and the selection from the logits tile, in one kernel
+      if (nt <= 1) launch_logits<1, 16, 4>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
+      else if (nt <= 2) launch_logits<2, 16, 4>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
+      else if (nt <= 4) launch_logits<4, 16, 2>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
+      else if (nt <= 8) launch_logits<8, 8, 1>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
+      else launch_logits<16, 4, 1>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
+      return hipGetLastError();
+    }
+    // few tokens, many experts: one workgroup per (16 tokens, 16 experts), then select from the logits
+    hipLaunchKernelGGL((router_logits_kernel<1, 16, 4, false>), dim3((T + kLogitTok - 1) / kLogitTok, nt),
+                       dim3(16 * 64), 0, stream, xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w);
+    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+    flags |= MOE_LOGITS_GIVEN;
   }
   const int epl = (E + kWave - 1) / kWave;
   switch (epl) {
