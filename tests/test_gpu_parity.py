@@ -48,7 +48,12 @@ def _route_gpu(x_bits, w_router, logits, T, H, E, k, renorm):
 @pytest.mark.parametrize("shape,T", [(I.TINY, 64), (I.MoEShape("q", 256, 60, 4, 128, False), 77),
                                      (I.MoEShape("wide", 128, 200, 6, 128, True), 33),
                                      (I.MoEShape("odd", 64, 13, 3, 128, True), 5),
-                                     (I.MoEShape("max", 192, 256, 16, 128, False), 40)])   # E and k at their limits
+                                     (I.MoEShape("max", 192, 256, 16, 128, False), 40),    # E and k at their limits
+                                     # more than 128 tokens: logits and selection in one kernel, 2 to 16 expert tiles
+                                     (I.MoEShape("q2", 256, 30, 4, 128, False), 300),
+                                     (I.MoEShape("q4", 256, 60, 4, 128, False), 333),
+                                     (I.MoEShape("q8", 128, 100, 6, 128, True), 200),
+                                     (I.MoEShape("q16", 128, 200, 6, 128, True), 300)])
 def test_route_logits_and_topk(shape, T):
     li = I.make_layer_inputs(shape, T, 0, weights=False)
     E, k = shape.n_experts, shape.top_k
