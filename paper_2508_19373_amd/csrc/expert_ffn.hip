@@ -22,7 +22,7 @@ namespace {
 
 // Prefill-sized groups: LDS-DMA kernel, 256-column tiles of 256 / 128 / 64 rows.
 template <int BN>
-hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, int cap_rows, int n_local, int H,
+hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, int cap_rows, int est_rows, int n_local, int H,
                             int I_s, const void* w_gate, const void* w_up, const void* w_down, void* h_ws,
                             void* y_perm, void* workspace, uint32_t flags, hipStream_t stream) {
   const bool y_bf16 = (flags & MOE_Y_PERM_BF16) != 0;
@@ -40,7 +40,7 @@ hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, i
   }
   if (flags & MOE_FFN_SKIP_DOWN) return hipSuccess;
   const int ncb = (H + BN - 1) / BN;
-  const int slices = (y_bf16 || workspace == nullptr) ? 1 : gg::k_slices_for(cap_rows, n_local, ncb, I_s);
+  const int slices = (y_bf16 || workspace == nullptr) ? 1 : gg::k_slices_for(est_rows, n_local, ncb, I_s);
   if (y_bf16) {
     hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, uint16_t>), grid_for(ncb), block, 0, stream, hw,
                        expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_down),
@@ -150,10 +150,13 @@ hipError_t launch_pair_decode(const void* x_perm, const int32_t* expert_offsets,
   return hipGetLastError();
 }
 
-// MT = 1 (16 activation rows per pass) when experts hold about 8 rows or fewer on average: it keeps
-// twice the bytes in flight, and the rare expert with more than 16 rows only pays a second pass
-// over its own weights.
-inline int decode_mt(int cap_rows, int n_local) { return (cap_rows <= 16 || cap_rows / n_local <= 8) ? 1 : 2; }
+// MT = 1 (16 activation rows per pass) when the fullest expert is expected to stay within 16 rows
+// (two-sigma margin on the average; certain when the whole capacity is 16 rows): it keeps twice
+// the bytes in flight, and an expert with more rows only pays another pass over its own weights.
+inline int decode_mt(int cap_rows, int est_rows, int n_local) {
+  const double avg = (double)est_rows / n_local;
+  return (cap_rows <= 16 || avg + 2.0 * sqrt(avg) <= 16.0) ? 1 : 2;
+}
 
 // Which kernel family runs one of the two GEMMs: the weight-streaming walk (decode regime) or the
 // tiled LDS-DMA kernel (prefill regime).  A few rows per expert are bound by streaming the
@@ -163,53 +166,54 @@ inline int decode_mt(int cap_rows, int n_local) { return (cap_rows <= 16 || cap_
 // projection of a single shared expert -- H / 256 = 14 tiles -- would use 14 CUs, which is why such
 // a launch is also cut along K).  Estimates in seconds from measured rates: walk 5.5 TB/s plus 5 us
 // per pass, tiled kernel min(5 TB/s, 40 GB/s per tile and K slice) and 1.2 PFLOP/s.  Routed experts get a two-sigma margin on the rows of the fullest expert.
-inline bool prefer_walk(int cap_rows, int n_local, int n_out, int K, bool gateup) {
+inline bool prefer_walk(int cap_rows, int est_rows, int n_local, int n_out, int K, bool gateup) {
   const double mats = gateup ? 2.0 : 1.0;
-  const double avg = (double)cap_rows / n_local;
-  const double rows_hi = n_local == 1 ? avg : avg + 2.0 * sqrt(avg);
-  const double passes = ceil(rows_hi / (decode_mt(cap_rows, n_local) == 1 ? 16.0 : 32.0));
+  const double avg = (double)est_rows / n_local;
+  const double rows_hi = (n_local == 1 && est_rows == cap_rows) ? avg : avg + 2.0 * sqrt(avg);  // one expert, every row: exact
+  const double passes = ceil(rows_hi / (decode_mt(cap_rows, est_rows, n_local) == 1 ? 16.0 : 32.0));
   const double bytes = mats * n_local * (double)n_out * K * 2.0;
   const double walk = passes * (bytes / 5.5e12 + 5e-6);  // a pass also pays its ramp-up
   const int ncb = (n_out + (gateup ? 127 : 255)) / (gateup ? 128 : 256);
-  const double tiles = (double)(cap_rows / 256 + n_local) * ncb * (gateup ? 1 : gg::k_slices_for(cap_rows, n_local, ncb, K));
+  const double tiles = (double)(est_rows / 256 + n_local) * ncb * (gateup ? 1 : gg::k_slices_for(est_rows, n_local, ncb, K));
   const double stream = bytes / fmin(5.0e12, tiles * 40e9);
-  const double mfma = 2.0 * mats * cap_rows * (double)n_out * K / 1.2e15;
+  const double mfma = 2.0 * mats * est_rows * (double)n_out * K / 1.2e15;
   return walk < fmax(stream, mfma);
 }
 
 }  // namespace
 
-size_t ffn_workspace_bytes(int cap_rows, int n_local, int H, int I_s) {
+size_t ffn_workspace_bytes(int cap_rows, int est_rows, int n_local, int H, int I_s) {
   if (cap_rows == 0) return 0;
   int slices;
-  if (prefer_walk(cap_rows, n_local, H, I_s, false)) {
-    const gw::WalkPlan p2 = gw::plan_for(I_s, decode_mt(cap_rows, n_local));
+  if (prefer_walk(cap_rows, est_rows, n_local, H, I_s, false)) {
+    const gw::WalkPlan p2 = gw::plan_for(I_s, decode_mt(cap_rows, est_rows, n_local));
     slices = p2.nw == 0 ? 1 : p2.slices;
   } else {
-    slices = gg::k_slices_for(cap_rows, n_local, (H + 255) / 256, I_s);
+    slices = gg::k_slices_for(est_rows, n_local, (H + 255) / 256, I_s);
   }
   return slices > 1 ? (size_t)slices * cap_rows * H * sizeof(float) : 0;
 }
 
-hipError_t launch_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int cap_rows, int n_local, int H,
+hipError_t launch_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int cap_rows, int est_rows, int n_local, int H,
                              int I_s, const void* w_gate, const void* w_up, const void* w_down, void* h_ws,
                              void* y_perm, void* workspace, size_t workspace_bytes, uint32_t flags,
                              hipStream_t stream) {
   (void)workspace_bytes;
   if (cap_rows == 0) return hipSuccess;
   // each GEMM picks its kernel family on its own: h is row-major bf16 for both
-  const int mt = decode_mt(cap_rows, n_local);
+  const int mt = decode_mt(cap_rows, est_rows, n_local);
   auto run = [&](bool walk, uint32_t f) {
     if (!walk)
-      return launch_pair_dlds<256>(x_perm, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,
-                                   y_perm, workspace, f, stream);
+      return launch_pair_dlds<256>(x_perm, expert_offsets, cap_rows, est_rows, n_local, H, I_s, w_gate, w_up, w_down,
+                                   h_ws, y_perm, workspace, f, stream);
     if (mt == 1)
       return launch_pair_decode<1>(x_perm, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,
                                    y_perm, workspace, f, stream);
     return launch_pair_decode<2>(x_perm, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,
                                  y_perm, workspace, f, stream);
   };
-  const bool walk1 = prefer_walk(cap_rows, n_local, I_s, H, true), walk2 = prefer_walk(cap_rows, n_local, H, I_s, false);
+  const bool walk1 = prefer_walk(cap_rows, est_rows, n_local, I_s, H, true),
+             walk2 = prefer_walk(cap_rows, est_rows, n_local, H, I_s, false);
   if (walk1 == walk2 || (flags & (MOE_FFN_SKIP_GATEUP | MOE_FFN_SKIP_DOWN)))
     return run((flags & MOE_FFN_SKIP_GATEUP) ? walk2 : walk1, flags);
   const hipError_t err = run(walk1, flags | MOE_FFN_SKIP_DOWN);

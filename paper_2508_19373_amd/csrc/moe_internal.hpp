@@ -41,10 +41,12 @@ hipError_t launch_permute(const void* x, const int32_t* topk_idx, int T, int k, 
                           void* x_perm, int32_t* expert_offsets, int32_t* row_src, int32_t* slot_row,
                           void* workspace, hipStream_t stream);
 size_t permute_workspace_bytes(int T, int k, int n_local);
-hipError_t launch_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int cap_rows, int n_local, int H,
+// est_rows: the rows this shard expects (cap_rows scaled by its share of the experts); it steers the
+// choice of kernels and K slices only, every bound is taken from cap_rows.
+hipError_t launch_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int cap_rows, int est_rows, int n_local, int H,
                              int I_s, const void* w_gate, const void* w_up, const void* w_down, void* h_ws,
                              void* y_perm, void* workspace, size_t workspace_bytes, uint32_t flags, hipStream_t stream);
-size_t ffn_workspace_bytes(int cap_rows, int n_local, int H, int I_s);
+size_t ffn_workspace_bytes(int cap_rows, int est_rows, int n_local, int H, int I_s);
 hipError_t launch_combine(const void* y_perm, const int32_t* slot_row, const float* topk_w, int T, int k, int H,
                           const void* y_shared, const void* x, const float* w_shared_gate, void* y_out,
                           bool y_perm_bf16, bool out_f32, hipStream_t stream);
