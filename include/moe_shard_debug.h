@@ -30,6 +30,16 @@ int32_t moe_debug_gemm_units(const int32_t* expert_offsets, int32_t n_local, int
                              int32_t n_col_blocks, int32_t* units,
                              int32_t max_units);
 
+/*
+ * Which kernels moe_expert_ffn would launch for (cap_rows, shard): the paper separates a
+ * memory-bound decoding regime from a compute-bound prefill regime ("Generative Inference"); the
+ * library picks, per GEMM, a weight-streaming kernel or a tiled MFMA kernel from a cost estimate.
+ * plan [4] int32 HOST: {GEMM1 streams weights (0/1), GEMM2 streams weights (0/1),
+ *                       activation rows per streaming pass / 16 (1 or 2), K slices of GEMM2}
+ * Returns MOE_OK or MOE_ERR_INVALID_ARG.
+ */
+int32_t moe_debug_ffn_plan(int32_t cap_rows, const moe_shard_t* shard, int32_t* plan);
+
 #ifdef __cplusplus
 }
 #endif

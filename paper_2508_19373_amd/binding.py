@@ -27,7 +27,7 @@ MOE_MAX_TOPK = 16
 
 EXPORTS = ("moe_route_topk", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_workspace_bytes",
            "moe_ffn_workspace_bytes", "moe_status_string")
-DEBUG_EXPORTS = ("moe_debug_gemm_units",)
+DEBUG_EXPORTS = ("moe_debug_gemm_units", "moe_debug_ffn_plan")
 INT4_EXPORTS = ("moe_int4_dequantize", "moe_int4_quantize")
 INT4_GROUP = 64
 DEBUG_UNIT_INTS = 5
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.moe_int4_dequantize.restype = ctypes.c_int
         L.moe_int4_quantize.argtypes = [vp, ctypes.c_int64, vp, vp, vp]
         L.moe_int4_quantize.restype = ctypes.c_int
+        L.moe_debug_ffn_plan.argtypes = [i32, shp, vp]
+        L.moe_debug_ffn_plan.restype = i32
         L.moe_debug_gemm_units.argtypes = [vp, i32, i32, i32, vp, i32]
         L.moe_debug_gemm_units.restype = i32
         _lib = L
@@ -168,3 +170,13 @@ def moe_debug_gemm_units(expert_offsets, cap_rows, n_col_blocks):
     if n < 0:
         raise MoeError("moe_debug_gemm_units", n)
     return out[:n]
+
+
+def moe_debug_ffn_plan(cap_rows, shard: MoeShard):
+    """Host-only: (GEMM1 by the streaming kernel, GEMM2 by the streaming kernel, rows per pass / 16,
+    K slices of GEMM2) that moe_expert_ffn would use (see include/moe_shard_debug.h)."""
+    plan = (ctypes.c_int32 * 4)()
+    st = lib().moe_debug_ffn_plan(cap_rows, ctypes.byref(shard), plan)
+    if st != MOE_OK:
+        raise MoeError("moe_debug_ffn_plan", st)
+    return bool(plan[0]), bool(plan[1]), int(plan[2]), int(plan[3])

@@ -2,6 +2,14 @@
 // Nothing here allocates or synchronises; every error is a return code.
 #include "moe_internal.hpp"
 
+namespace moe {
+// Rows an expert-parallel shard expects out of a capacity of T*k: its share of the experts.
+int expected_rows(int cap_rows, const moe_shard_t* s) {
+  const int64_t est = (int64_t)cap_rows * s->n_local_experts / s->n_experts;
+  return est < 1 ? (cap_rows > 0 ? 1 : 0) : (int)est;
+}
+}  // namespace moe
+
 namespace {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -19,11 +27,6 @@ int shard_status(const moe_shard_t* s) {
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_HIP; }
 
-// Rows an expert-parallel shard expects out of a capacity of T*k: its share of the experts.
-inline int expected_rows(int cap_rows, const moe_shard_t* s) {
-  const int64_t est = (int64_t)cap_rows * s->n_local_experts / s->n_experts;
-  return est < 1 ? (cap_rows > 0 ? 1 : 0) : (int)est;
-}
 
 }  // namespace
 
@@ -50,7 +53,7 @@ size_t moe_workspace_bytes(int32_t T, int32_t k, const moe_shard_t* shard) {
 
 size_t moe_ffn_workspace_bytes(int32_t cap_rows, const moe_shard_t* shard) {
   if (cap_rows < 0 || shard_status(shard) != MOE_OK) return 0;
-  return moe::ffn_workspace_bytes(cap_rows, expected_rows(cap_rows, shard), shard->n_local_experts, shard->hidden,
+  return moe::ffn_workspace_bytes(cap_rows, moe::expected_rows(cap_rows, shard), shard->n_local_experts, shard->hidden,
                                   shard->inter_slice);
 }
 
@@ -88,7 +91,7 @@ int moe_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int32_t ca
     return MOE_ERR_INVALID_ARG;
   const size_t need = moe_ffn_workspace_bytes(cap_rows, shard);
   if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned16(workspace))) return MOE_ERR_WORKSPACE;
-  return hip_status(moe::launch_expert_ffn(x_perm, expert_offsets, cap_rows, expected_rows(cap_rows, shard),
+  return hip_status(moe::launch_expert_ffn(x_perm, expert_offsets, cap_rows, moe::expected_rows(cap_rows, shard),
                                            shard->n_local_experts, shard->hidden,
                                            shard->inter_slice, w_gate, w_up, w_down, h_workspace, y_perm, workspace,
                                            workspace_bytes, flags, static_cast<hipStream_t>(stream)));

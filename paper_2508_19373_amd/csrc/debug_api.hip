@@ -2,6 +2,7 @@
 // integer logic the kernel runs per workgroup, so CPU tests can check that every tile of every
 // routing is covered exactly once.
 #include "moe_shard_debug.h"
+#include "moe_internal.hpp"
 #include "unit_list.hpp"
 
 extern "C" int32_t moe_debug_gemm_units(const int32_t* expert_offsets, int32_t n_local, int32_t cap_rows,
@@ -29,4 +30,14 @@ extern "C" int32_t moe_debug_gemm_units(const int32_t* expert_offsets, int32_t n
     rec[4] = tc.nb;
   }
   return grid;
+}
+
+extern "C" int32_t moe_debug_ffn_plan(int32_t cap_rows, const moe_shard_t* shard, int32_t* plan) {
+  if (cap_rows < 0 || shard == nullptr || plan == nullptr) return MOE_ERR_INVALID_ARG;
+  if (shard->n_experts < 1 || shard->n_local_experts < 1 || shard->n_local_experts > shard->n_experts ||
+      shard->hidden < 64 || shard->inter_slice < 64)
+    return MOE_ERR_INVALID_ARG;
+  moe::ffn_plan(cap_rows, moe::expected_rows(cap_rows, shard), shard->n_local_experts, shard->hidden,
+                shard->inter_slice, plan);
+  return MOE_OK;
 }

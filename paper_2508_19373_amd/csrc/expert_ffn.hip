@@ -6,10 +6,12 @@
 // Two grouped GEMMs, both "NT" (activations and weights are K-contiguous):
 //   GEMM1  h[r, i]  = silu(x_r . Wg_e[i,:]) * (x_r . Wu_e[i,:])      K = H,   N = I_s (gate+up fused)
 //   GEMM2  y[r, n]  = h_r . Wd_e[n,:]                                K = I_s, N = H
-// bf16 operands, fp32 accumulators.  Two kernels cover the two regimes the paper distinguishes
-// ("Generative Inference"): grouped_gemm.hpp for compute-bound prefill-sized groups and
-// grouped_stream.hpp for memory-bound decode-sized groups.  In both, the work list is derived
-// on the device from expert_offsets without a host round trip.
+// bf16 operands, fp32 accumulators.  Two kernel families cover the two regimes the paper
+// distinguishes ("Generative Inference"): grouped_gemm.hpp (tiled, LDS-DMA, MFMA-bound) for
+// prefill-sized groups, grouped_walk.hpp (weight streaming, HBM-bound; grouped_stream.hpp for the
+// K extents it is not instantiated for) for decode-sized groups.  Each of the two GEMMs picks its
+// family from a cost estimate (prefer_walk below).  In both, the work list is derived on the
+// device from expert_offsets without a host round trip.
 #include "grouped_gemm.hpp"
 #include "grouped_stream.hpp"
 #include "grouped_walk.hpp"
@@ -40,7 +42,7 @@ hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, i
   }
   if (flags & MOE_FFN_SKIP_DOWN) return hipSuccess;
   const int ncb = (H + BN - 1) / BN;
-  const int slices = (y_bf16 || workspace == nullptr) ? 1 : gg::k_slices_for(est_rows, n_local, ncb, I_s);
+  const int slices = (y_bf16 || workspace == nullptr) ? 1 : gg::k_slices_for(est_rows, n_local, ncb, I_s, n_local == 1 && est_rows == cap_rows);
   if (y_bf16) {
     hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, uint16_t>), grid_for(ncb), block, 0, stream, hw,
                        expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_down),
@@ -162,22 +164,30 @@ inline int decode_mt(int cap_rows, int est_rows, int n_local) {
 // tiled LDS-DMA kernel (prefill regime).  A few rows per expert are bound by streaming the
 // weights once, many rows by the matrix cores; in between, what decides is how often the walk has
 // to re-stream an expert (one pass per 16 or 32 rows) against how many tiles the tiled kernel can
-// spread over the compute units (a tile streams its weight panel at about 40 GB/s, so a down
-// projection of a single shared expert -- H / 256 = 14 tiles -- would use 14 CUs, which is why such
-// a launch is also cut along K).  Estimates in seconds from measured rates: walk 5.5 TB/s plus 5 us
-// per pass, tiled kernel min(5 TB/s, 40 GB/s per tile and K slice) and 1.2 PFLOP/s.  Routed experts get a two-sigma margin on the rows of the fullest expert.
+// spread over the compute units (the down projection of a single shared expert has H / 256 = 14
+// column blocks per row block: 14 CUs, which is why such a launch is also cut along K).
+// Estimates in seconds, from measured rates on MI355X:
+//   walk   passes * (bytes / rate + 5 us), rate 6.0 / 5.4 TB/s (GEMM1 / GEMM2) at 16 rows per pass,
+//          5.6 / 4.9 TB/s at 32; passes from the rows of the fullest expert (two-sigma margin);
+//   tiled  rounds * (weight bytes of one tile and K slice / 21 GB/s + 8 us) with rounds = tiles *
+//          slices / 256, at least one (a compute unit streams a tile's panel latency-bound), and
+//          no faster than 5.6 TB/s overall or 1.2 PFLOP/s.
 inline bool prefer_walk(int cap_rows, int est_rows, int n_local, int n_out, int K, bool gateup) {
   const double mats = gateup ? 2.0 : 1.0;
   const double avg = (double)est_rows / n_local;
-  const double rows_hi = (n_local == 1 && est_rows == cap_rows) ? avg : avg + 2.0 * sqrt(avg);  // one expert, every row: exact
-  const double passes = ceil(rows_hi / (decode_mt(cap_rows, est_rows, n_local) == 1 ? 16.0 : 32.0));
+  const bool exact = n_local == 1 && est_rows == cap_rows;  // one expert that takes every row
+  const double rows_hi = exact ? avg : avg + 2.0 * sqrt(avg);
+  const int mt = decode_mt(cap_rows, est_rows, n_local);
+  const double passes = ceil(rows_hi / (16.0 * mt));
   const double bytes = mats * n_local * (double)n_out * K * 2.0;
-  const double walk = passes * (bytes / 5.5e12 + 5e-6);  // a pass also pays its ramp-up
+  const double rate = mt == 1 ? (gateup ? 6.0e12 : 5.4e12) : (gateup ? 5.6e12 : 4.9e12);
+  const double walk = passes * (bytes / rate + 5e-6);
   const int ncb = (n_out + (gateup ? 127 : 255)) / (gateup ? 128 : 256);
-  const double tiles = (double)(est_rows / 256 + n_local) * ncb * (gateup ? 1 : gg::k_slices_for(est_rows, n_local, ncb, K));
-  const double stream = bytes / fmin(5.0e12, tiles * 40e9);
-  const double mfma = 2.0 * mats * est_rows * (double)n_out * K / 1.2e15;
-  return walk < fmax(stream, mfma);
+  const int slices = gateup ? 1 : gg::k_slices_for(est_rows, n_local, ncb, K, exact);
+  const double units = (double)gg::expected_tiles(est_rows, n_local, ncb, exact) * slices;
+  const double tile = 256.0 * (K / slices) * 2.0 / 21e9 + 8e-6;
+  const double tiled = fmax(fmax(units / 256.0, 1.0) * tile, fmax(bytes / 5.6e12, 2.0 * mats * est_rows * (double)n_out * K / 1.2e15));
+  return walk < tiled;
 }
 
 }  // namespace
@@ -189,9 +199,24 @@ size_t ffn_workspace_bytes(int cap_rows, int est_rows, int n_local, int H, int I
     const gw::WalkPlan p2 = gw::plan_for(I_s, decode_mt(cap_rows, est_rows, n_local));
     slices = p2.nw == 0 ? 1 : p2.slices;
   } else {
-    slices = gg::k_slices_for(est_rows, n_local, (H + 255) / 256, I_s);
+    slices = gg::k_slices_for(est_rows, n_local, (H + 255) / 256, I_s, n_local == 1 && est_rows == cap_rows);
   }
   return slices > 1 ? (size_t)slices * cap_rows * H * sizeof(float) : 0;
+}
+
+void ffn_plan(int cap_rows, int est_rows, int n_local, int H, int I_s, int32_t out[4]) {
+  const bool walk1 = prefer_walk(cap_rows, est_rows, n_local, I_s, H, true),
+             walk2 = prefer_walk(cap_rows, est_rows, n_local, H, I_s, false);
+  const int mt = decode_mt(cap_rows, est_rows, n_local);
+  out[0] = walk1;
+  out[1] = walk2;
+  out[2] = mt;
+  if (walk2) {
+    const gw::WalkPlan p2 = gw::plan_for(I_s, mt);
+    out[3] = p2.nw == 0 ? 1 : p2.slices;
+  } else {
+    out[3] = gg::k_slices_for(est_rows, n_local, (H + 255) / 256, I_s, n_local == 1 && est_rows == cap_rows);
+  }
 }
 
 hipError_t launch_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int cap_rows, int est_rows, int n_local, int H,

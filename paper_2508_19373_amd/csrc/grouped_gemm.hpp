@@ -24,6 +24,7 @@
 //    on a contiguous run of tiles that share A and B panels in its own L2; remainder tiles run
 //    after all full tiles, so concurrent full tiles stay in k-lockstep (see find_unit).
 #pragma once
+#include <cmath>
 #include <type_traits>
 
 #include "moe_internal.hpp"
@@ -348,11 +349,20 @@ __global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
     gemm_tile<64, BN, 1, 4, 4, 4, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out);
 }
 
+// Tiles a launch is expected to have: every local expert with its expected rows plus a two-sigma
+// margin (none when `exact`: one expert that takes every row), in 256-row blocks (a remainder tile
+// counts as a block).
+inline int expected_tiles(int est_rows, int n_local, int n_col_blocks, bool exact) {
+  const double avg = (double)est_rows / n_local;
+  const int blocks = (int)((avg + (exact ? 0.0 : 2.0 * sqrt(avg)) + 255.0) / 256.0);
+  return n_local * (blocks < 1 ? 1 : blocks) * n_col_blocks;
+}
+
 // K slices for a down projection whose tile count would leave most compute units idle (a single
 // shared expert with a few hundred rows: H / 256 column blocks per row block): the largest of 8, 4,
 // 2 that divides the k-tile count, keeps at least 8 k-tiles per slice and at most 256 workgroups.
-inline int k_slices_for(int cap_rows, int n_local, int n_col_blocks, int K) {
-  const int tiles = (cap_rows / 256 + n_local) * n_col_blocks, nk = K / BK;
+inline int k_slices_for(int est_rows, int n_local, int n_col_blocks, int K, bool exact) {
+  const int tiles = expected_tiles(est_rows, n_local, n_col_blocks, exact), nk = K / BK;
   for (int s = 8; s >= 2; s >>= 1)
     if (tiles * s <= 256 && nk % s == 0 && nk / s >= 8) return s;
   return 1;

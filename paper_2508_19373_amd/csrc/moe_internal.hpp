@@ -47,6 +47,10 @@ hipError_t launch_expert_ffn(const void* x_perm, const int32_t* expert_offsets, 
                              int I_s, const void* w_gate, const void* w_up, const void* w_down, void* h_ws,
                              void* y_perm, void* workspace, size_t workspace_bytes, uint32_t flags, hipStream_t stream);
 size_t ffn_workspace_bytes(int cap_rows, int est_rows, int n_local, int H, int I_s);
+// What launch_expert_ffn would do: {GEMM1 by the walk kernel, GEMM2 by the walk kernel, rows per
+// walk pass / 16, K slices of GEMM2}.
+void ffn_plan(int cap_rows, int est_rows, int n_local, int H, int I_s, int32_t out[4]);
+int expected_rows(int cap_rows, const moe_shard_t* shard);
 hipError_t launch_combine(const void* y_perm, const int32_t* slot_row, const float* topk_w, int T, int k, int H,
                           const void* y_shared, const void* x, const float* w_shared_gate, void* y_out,
                           bool y_perm_bf16, bool out_f32, hipStream_t stream);

@@ -144,7 +144,7 @@ def test_expert_ffn_validation(lib):
     assert B.moe_ffn_workspace_bytes(8192, mix) == 0
     # a single expert with a few hundred rows: the tiled down projection is cut along K
     one = _shard(n_experts=1, n_local_experts=1, hidden=3584, inter_full=20480, inter_slice=20480)
-    assert B.moe_ffn_workspace_bytes(1024, one) == 2 * 1024 * 3584 * 4   # up to 5 row blocks x 14 column blocks x 2 slices
+    assert B.moe_ffn_workspace_bytes(1024, one) == 4 * 1024 * 3584 * 4   # 4 row blocks x 14 column blocks x 4 slices
     assert f(P, P, 32, ctypes.byref(mix), P, P, P, P, P, None, 0, 0, None) == B.MOE_ERR_WORKSPACE
     assert f(P, P, 32, ctypes.byref(mix), P, P, P, P, P, P, need - 1, 0, None) == B.MOE_ERR_WORKSPACE
 
