@@ -168,10 +168,12 @@ inline int decode_mt(int cap_rows, int est_rows, int n_local) {
 // column blocks per row block: 14 CUs, which is why such a launch is also cut along K).
 // Estimates in seconds, from measured rates on MI355X:
 //   walk   passes * (bytes / rate + 5 us), rate 6.0 / 5.4 TB/s (GEMM1 / GEMM2) at 16 rows per pass,
-//          5.6 / 4.9 TB/s at 32; passes from the rows of the fullest expert (two-sigma margin);
-//   tiled  rounds * (weight bytes of one tile and K slice / 21 GB/s + 8 us) with rounds = tiles *
-//          slices / 256, at least one (a compute unit streams a tile's panel latency-bound), and
-//          no faster than 5.6 TB/s overall or 1.2 PFLOP/s.
+//          5.6 / 4.9 TB/s at 32, 3 TB/s for K extents only the generic streaming kernel covers;
+//          passes from the rows of the fullest expert (two-sigma margin);
+//   tiled  rounds * (tile time + 8 us), rounds = tiles * slices / 256, at least one; tile time is
+//          the larger of streaming the tile's weight panel (latency-bound 45 GB/s per compute unit,
+//          less when the busy units together would exceed 5.4 TB/s) and its MFMA pace (1.3 us per
+//          k-tile of a full 256-row tile); never faster than 1.2 PFLOP/s overall.
 inline bool prefer_walk(int cap_rows, int est_rows, int n_local, int n_out, int K, bool gateup) {
   const double mats = gateup ? 2.0 : 1.0;
   const double avg = (double)est_rows / n_local;
@@ -180,13 +182,16 @@ inline bool prefer_walk(int cap_rows, int est_rows, int n_local, int n_out, int 
   const int mt = decode_mt(cap_rows, est_rows, n_local);
   const double passes = ceil(rows_hi / (16.0 * mt));
   const double bytes = mats * n_local * (double)n_out * K * 2.0;
-  const double rate = mt == 1 ? (gateup ? 6.0e12 : 5.4e12) : (gateup ? 5.6e12 : 4.9e12);
+  const double rate = gw::plan_for(K, mt).nw == 0 ? 3.0e12
+                                                  : (mt == 1 ? (gateup ? 6.0e12 : 5.4e12) : (gateup ? 5.6e12 : 4.9e12));
   const double walk = passes * (bytes / rate + 5e-6);
   const int ncb = (n_out + (gateup ? 127 : 255)) / (gateup ? 128 : 256);
   const int slices = gateup ? 1 : gg::k_slices_for(est_rows, n_local, ncb, K, exact);
   const double units = (double)gg::expected_tiles(est_rows, n_local, ncb, exact) * slices;
-  const double tile = 256.0 * (K / slices) * 2.0 / 21e9 + 8e-6;
-  const double tiled = fmax(fmax(units / 256.0, 1.0) * tile, fmax(bytes / 5.6e12, 2.0 * mats * est_rows * (double)n_out * K / 1.2e15));
+  const double per_cu = fmin(45e9, 5.4e12 / fmin(units, 256.0));
+  const double k_slice = (double)K / slices;
+  const double tile = fmax(256.0 * k_slice * 2.0 / per_cu, k_slice / 64.0 * 1.3e-6 * fmin(1.0, rows_hi / 256.0)) + 8e-6;
+  const double tiled = fmax(fmax(units / 256.0, 1.0) * tile, 2.0 * mats * est_rows * (double)n_out * K / 1.2e15);
   return walk < tiled;
 }
 

@@ -31,8 +31,7 @@ def test_routed_experts_switch_regime_near_twenty_rows_per_expert():
 def test_single_shared_expert_never_runs_its_down_projection_on_a_handful_of_tiles():
     s = _shard(1, 1, hidden=3584, inter_full=20480, inter_slice=20480)   # H / 256 = 14 column blocks
     assert B.moe_debug_ffn_plan(32, s)[:2] == (True, True)               # decode: stream both
-    assert B.moe_debug_ffn_plan(64, s)[:2] == (False, True)              # two passes: only the 14-tile GEMM streams
-    for rows in (128, 256, 512, 1024):
+    for rows in (64, 128, 256, 512, 1024):
         w1, w2, mt, slices = B.moe_debug_ffn_plan(rows, s)
         assert not w1 and not w2 and slices >= 2, rows
     assert B.moe_debug_ffn_plan(256, s) == (False, False, 2, 8)
@@ -51,6 +50,13 @@ def test_expert_parallel_shard_is_planned_on_its_expected_rows():
     # decode: 16 rows expected on the one local expert, but up to 128 possible: 32 rows per pass
     assert B.moe_debug_ffn_plan(128, ep8)[2] == 2
     assert B.moe_debug_ffn_plan(16, ep8)[2] == 1            # capacity itself is 16 rows
+
+
+def test_k_extents_without_a_fast_streaming_kernel_go_to_the_tiled_kernel_early():
+    # Qwen1.5-MoE under TP 4: the padded slice is 384 wide, a K extent only the generic streaming kernel covers
+    s = B.make_shard(60, 60, 0, 2048, 1536, 384)
+    w1, w2, mt, slices = B.moe_debug_ffn_plan(64 * 4, s)
+    assert w1 and not w2
 
 
 def test_invalid_arguments():
