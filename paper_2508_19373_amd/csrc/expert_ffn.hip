@@ -34,7 +34,7 @@ hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, i
   auto grid_for = [&](int ncb) { return dim3((unsigned)gg::max_grid(cap_rows, n_local, ncb)); };
   if (!(flags & MOE_FFN_SKIP_GATEUP)) {
     const int ncb = (I_s + BN / 2 - 1) / (BN / 2);
-    hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, true, uint16_t>), grid_for(ncb), block, 0, stream, xp,
+    hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, true, uint16_t, false>), grid_for(ncb), block, 0, stream, xp,
                        expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_gate),
                        static_cast<const uint16_t*>(w_up), I_s, H, hw, ncb);
     hipError_t err = hipGetLastError();
@@ -44,16 +44,21 @@ hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, i
   const int ncb = (H + BN - 1) / BN;
   const int slices = (y_bf16 || workspace == nullptr) ? 1 : gg::k_slices_for(est_rows, n_local, ncb, I_s, n_local == 1 && est_rows == cap_rows);
   if (y_bf16) {
-    hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, uint16_t>), grid_for(ncb), block, 0, stream, hw,
+    hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, uint16_t, false>), grid_for(ncb), block, 0, stream, hw,
                        expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_down),
                        static_cast<const uint16_t*>(nullptr), H, I_s, static_cast<uint16_t*>(y_perm), ncb);
     return hipGetLastError();
   }
   dim3 grid = grid_for(ncb);
   grid.y = slices;
-  hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, float>), grid, block, 0, stream, hw, expert_offsets,
-                     n_local, cap_rows, static_cast<const uint16_t*>(w_down), static_cast<const uint16_t*>(nullptr),
-                     H, I_s, static_cast<float*>(slices > 1 ? workspace : y_perm), ncb);
+  if (slices == 1)
+    hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, float, false>), grid, block, 0, stream, hw,
+                       expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_down),
+                       static_cast<const uint16_t*>(nullptr), H, I_s, static_cast<float*>(y_perm), ncb);
+  else
+    hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, float, true>), grid, block, 0, stream, hw,
+                       expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_down),
+                       static_cast<const uint16_t*>(nullptr), H, I_s, static_cast<float*>(workspace), ncb);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess || slices == 1) return err;
   hipLaunchKernelGGL(gw::sum_slices_kernel, dim3(256), dim3(256), 0, stream, static_cast<const float*>(workspace),

@@ -326,11 +326,12 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
 }
 
 // Kernel: 256 threads (4 wavefronts); each workgroup computes one tile, whose height class
-// selects the wave arrangement and the LDS stage counts.  grid.y = K slices: slice z covers k-tiles
-// [z, z+1) * K / 64 / gridDim.y and writes its partial sums to C + z * cap_rows * n_out (a launch
-// whose tiles would fill less than half the compute units is cut along K; the caller adds the
-// slices in order).
-template <int BN, bool GATEUP, typename OutT>
+// selects the wave arrangement and the LDS stage counts.  SLICED: grid.y = K slices, slice z covers
+// k-tiles [z, z+1) * K / 64 / gridDim.y and writes its partial sums to C + z * cap_rows * n_out (a
+// launch whose tiles would fill less than half the compute units is cut along K; the caller adds
+// the slices in order).  A separate instantiation, so that the unsliced kernels keep their
+// register allocation (the extra live values cost the main path 2-3 %).
+template <int BN, bool GATEUP, typename OutT, bool SLICED>
 __global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
     const uint16_t* __restrict__ A, const int32_t* __restrict__ expert_offsets, int n_local, int cap_rows,
     const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1, int n_out, int K, OutT* __restrict__ C,
@@ -339,8 +340,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
   const Unit u = find_unit(count_tiles(expert_offsets, n_local, n_col_blocks), blockIdx.x);
   if (u.cls < 0) return;
   const TileCoord tc = locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx);
-  const int nk = K / BK / gridDim.y, kt0 = blockIdx.y * nk;
-  OutT* out = C + (size_t)blockIdx.y * cap_rows * n_out;
+  const int nk = SLICED ? K / BK / gridDim.y : K / BK, kt0 = SLICED ? blockIdx.y * nk : 0;
+  OutT* out = SLICED ? C + (size_t)blockIdx.y * cap_rows * n_out : C;
   if (u.cls == 0)
     gemm_tile<256, BN, 2, 2, 2, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out);
   else if (u.cls == 1)
