@@ -35,10 +35,22 @@ int32_t moe_debug_gemm_units(const int32_t* expert_offsets, int32_t n_local, int
  * memory-bound decoding regime from a compute-bound prefill regime ("Generative Inference"); the
  * library picks, per GEMM, a weight-streaming kernel or a tiled MFMA kernel from a cost estimate.
  * plan [4] int32 HOST: {GEMM1 streams weights (0/1), GEMM2 streams weights (0/1),
- *                       activation rows per streaming pass / 16 (1 or 2), K slices of GEMM2}
+ *                       activation rows per streaming pass / 16 (1 or 2), K slices of GEMM2 (for a
+ *                       tiled GEMM2 on a shard with few experts: the most the routing can select)}
  * Returns MOE_OK or MOE_ERR_INVALID_ARG.
  */
 int32_t moe_debug_ffn_plan(int32_t cap_rows, const moe_shard_t* shard, int32_t* plan);
+
+/*
+ * K slices the tiled down projection of moe_expert_ffn uses for one routing.  An expert-parallel
+ * shard's load follows the routing ("Parallelism in Inference": expert parallelism suffers from
+ * load imbalance), so for shards with few experts the kernel itself decides, from expert_offsets,
+ * how far a launch with few tiles is cut along K; this call runs the same decision on the host.
+ * expert_offsets [n_local+1] int32 HOST, as for moe_debug_gemm_units.
+ * Returns the number of slices (1 = unsliced) or a negative MOE_ERR_* code (MOE_ERR_WORKSPACE if
+ * the partial sums would not fit what moe_ffn_workspace_bytes asks for: never, by construction).
+ */
+int32_t moe_debug_down_slices(const int32_t* expert_offsets, int32_t cap_rows, const moe_shard_t* shard);
 
 #ifdef __cplusplus
 }

@@ -27,7 +27,7 @@ MOE_MAX_TOPK = 16
 
 EXPORTS = ("moe_route_topk", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_workspace_bytes",
            "moe_ffn_workspace_bytes", "moe_status_string")
-DEBUG_EXPORTS = ("moe_debug_gemm_units", "moe_debug_ffn_plan")
+DEBUG_EXPORTS = ("moe_debug_gemm_units", "moe_debug_ffn_plan", "moe_debug_down_slices")
 INT4_EXPORTS = ("moe_int4_dequantize", "moe_int4_quantize")
 INT4_GROUP = 64
 DEBUG_UNIT_INTS = 5
@@ -74,6 +74,8 @@ def lib() -> ctypes.CDLL:
         L.moe_int4_quantize.restype = ctypes.c_int
         L.moe_debug_ffn_plan.argtypes = [i32, shp, vp]
         L.moe_debug_ffn_plan.restype = i32
+        L.moe_debug_down_slices.argtypes = [vp, i32, shp]
+        L.moe_debug_down_slices.restype = i32
         L.moe_debug_gemm_units.argtypes = [vp, i32, i32, i32, vp, i32]
         L.moe_debug_gemm_units.restype = i32
         _lib = L
@@ -170,6 +172,19 @@ def moe_debug_gemm_units(expert_offsets, cap_rows, n_col_blocks):
     if n < 0:
         raise MoeError("moe_debug_gemm_units", n)
     return out[:n]
+
+
+def moe_debug_down_slices(expert_offsets, cap_rows, shard: MoeShard):
+    """Host-only: K slices the tiled down projection uses for this routing (see
+    include/moe_shard_debug.h).  `expert_offsets` is a host sequence."""
+    import numpy as np
+    offs = np.ascontiguousarray(expert_offsets, dtype=np.int32)
+    if offs.size != shard.n_local_experts + 1:
+        raise ValueError("expert_offsets must have n_local_experts + 1 entries")
+    n = lib().moe_debug_down_slices(offs.ctypes.data, cap_rows, ctypes.byref(shard))
+    if n < 0:
+        raise MoeError("moe_debug_down_slices", n)
+    return n
 
 
 def moe_debug_ffn_plan(cap_rows, shard: MoeShard):

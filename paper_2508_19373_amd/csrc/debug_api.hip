@@ -41,3 +41,23 @@ extern "C" int32_t moe_debug_ffn_plan(int32_t cap_rows, const moe_shard_t* shard
                 shard->inter_slice, plan);
   return MOE_OK;
 }
+
+extern "C" int32_t moe_debug_down_slices(const int32_t* expert_offsets, int32_t cap_rows, const moe_shard_t* shard) {
+  if (expert_offsets == nullptr || cap_rows < 0 || shard == nullptr) return MOE_ERR_INVALID_ARG;
+  if (shard->n_experts < 1 || shard->n_local_experts < 1 || shard->n_local_experts > shard->n_experts ||
+      shard->hidden < 64 || shard->inter_slice < 64)
+    return MOE_ERR_INVALID_ARG;
+  const int n_local = shard->n_local_experts;
+  for (int e = 0; e < n_local; ++e)
+    if (expert_offsets[e] > expert_offsets[e + 1]) return MOE_ERR_INVALID_ARG;
+  if (expert_offsets[0] < 0 || expert_offsets[n_local] > cap_rows) return MOE_ERR_INVALID_ARG;
+  using namespace moe::gg;
+  const int ncb = (shard->hidden + 255) / 256;
+  const SlicePlan sp =
+      slice_plan(cap_rows, moe::expected_rows(cap_rows, shard), n_local, ncb, shard->inter_slice);
+  if (!sp.adaptive) return sp.slices;
+  const ClassCounts cc = count_tiles(expert_offsets, n_local, ncb);
+  const int used = adaptive_slices(cc.n[0] + cc.n[1] + cc.n[2], shard->inter_slice / 64, sp.slices);
+  if ((long)used * expert_offsets[n_local] > sp.scratch_rows && used > 1) return MOE_ERR_WORKSPACE;
+  return used;
+}

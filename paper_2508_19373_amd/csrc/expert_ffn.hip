@@ -36,33 +36,43 @@ hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, i
     const int ncb = (I_s + BN / 2 - 1) / (BN / 2);
     hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, true, uint16_t, false>), grid_for(ncb), block, 0, stream, xp,
                        expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_gate),
-                       static_cast<const uint16_t*>(w_up), I_s, H, hw, ncb);
+                       static_cast<const uint16_t*>(w_up), I_s, H, hw, ncb, static_cast<uint16_t*>(nullptr), 0);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
   }
   if (flags & MOE_FFN_SKIP_DOWN) return hipSuccess;
   const int ncb = (H + BN - 1) / BN;
-  const int slices = (y_bf16 || workspace == nullptr) ? 1 : gg::k_slices_for(est_rows, n_local, ncb, I_s, n_local == 1 && est_rows == cap_rows);
   if (y_bf16) {
     hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, uint16_t, false>), grid_for(ncb), block, 0, stream, hw,
                        expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_down),
-                       static_cast<const uint16_t*>(nullptr), H, I_s, static_cast<uint16_t*>(y_perm), ncb);
+                       static_cast<const uint16_t*>(nullptr), H, I_s, static_cast<uint16_t*>(y_perm), ncb,
+                       static_cast<uint16_t*>(nullptr), 0);
     return hipGetLastError();
   }
+  const gg::SlicePlan sp = workspace == nullptr ? gg::SlicePlan{1, false, 0}
+                                                : gg::slice_plan(cap_rows, est_rows, n_local, ncb, I_s);
   dim3 grid = grid_for(ncb);
-  grid.y = slices;
-  if (slices == 1)
+  grid.y = sp.slices;
+  float* yp = static_cast<float*>(y_perm);
+  float* ws = static_cast<float*>(workspace);
+  const uint16_t* wd = static_cast<const uint16_t*>(w_down);
+  if (sp.slices == 1) {
     hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, float, false>), grid, block, 0, stream, hw,
-                       expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_down),
-                       static_cast<const uint16_t*>(nullptr), H, I_s, static_cast<float*>(y_perm), ncb);
-  else
-    hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, float, true>), grid, block, 0, stream, hw,
-                       expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_down),
-                       static_cast<const uint16_t*>(nullptr), H, I_s, static_cast<float*>(workspace), ncb);
+                       expert_offsets, n_local, cap_rows, wd, static_cast<const uint16_t*>(nullptr), H, I_s, yp, ncb,
+                       static_cast<float*>(nullptr), 0);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, float, true>), grid, block, 0, stream, hw,
+                     expert_offsets, n_local, cap_rows, wd, static_cast<const uint16_t*>(nullptr), H, I_s, ws, ncb, yp,
+                     sp.adaptive ? 1 : 0);
   hipError_t err = hipGetLastError();
-  if (err != hipSuccess || slices == 1) return err;
-  hipLaunchKernelGGL(gw::sum_slices_kernel, dim3(256), dim3(256), 0, stream, static_cast<const float*>(workspace),
-                     expert_offsets, n_local, cap_rows, H, slices, static_cast<float*>(y_perm));
+  if (err != hipSuccess) return err;
+  if (sp.adaptive)
+    hipLaunchKernelGGL(gg::sum_adaptive_slices_kernel, dim3(256), dim3(256), 0, stream, ws, expert_offsets, n_local,
+                       ncb, I_s / gg::BK, sp.slices, H, yp);
+  else
+    hipLaunchKernelGGL(gw::sum_slices_kernel, dim3(256), dim3(256), 0, stream, ws, expert_offsets, n_local, cap_rows,
+                       H, sp.slices, yp);
   return hipGetLastError();
 }
 
@@ -209,7 +219,8 @@ size_t ffn_workspace_bytes(int cap_rows, int est_rows, int n_local, int H, int I
     const gw::WalkPlan p2 = gw::plan_for(I_s, decode_mt(cap_rows, est_rows, n_local));
     slices = p2.nw == 0 ? 1 : p2.slices;
   } else {
-    slices = gg::k_slices_for(est_rows, n_local, (H + 255) / 256, I_s, n_local == 1 && est_rows == cap_rows);
+    const gg::SlicePlan sp = gg::slice_plan(cap_rows, est_rows, n_local, (H + 255) / 256, I_s);
+    return (size_t)sp.scratch_rows * H * sizeof(float);
   }
   return slices > 1 ? (size_t)slices * cap_rows * H * sizeof(float) : 0;
 }
@@ -225,7 +236,7 @@ void ffn_plan(int cap_rows, int est_rows, int n_local, int H, int I_s, int32_t o
     const gw::WalkPlan p2 = gw::plan_for(I_s, mt);
     out[3] = p2.nw == 0 ? 1 : p2.slices;
   } else {
-    out[3] = gg::k_slices_for(est_rows, n_local, (H + 255) / 256, I_s, n_local == 1 && est_rows == cap_rows);
+    out[3] = gg::slice_plan(cap_rows, est_rows, n_local, (H + 255) / 256, I_s).slices;
   }
 }
 

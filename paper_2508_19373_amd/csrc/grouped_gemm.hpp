@@ -329,19 +329,34 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
 // selects the wave arrangement and the LDS stage counts.  SLICED: grid.y = K slices, slice z covers
 // k-tiles [z, z+1) * K / 64 / gridDim.y and writes its partial sums to C + z * cap_rows * n_out (a
 // launch whose tiles would fill less than half the compute units is cut along K; the caller adds
-// the slices in order).  A separate instantiation, so that the unsliced kernels keep their
-// register allocation (the extra live values cost the main path 2-3 %).
+// the slices in order).  With `adaptive` the number of slices actually used follows the routing
+// (adaptive_slices on the real tile count): partial sums then go to C + z * R * n_out, R the
+// shard's actual rows, and an unsliced run writes `direct`.  A separate instantiation, so that the unsliced kernels keep
+// their register allocation (the extra live values cost the main path 2-3 %).
 template <int BN, bool GATEUP, typename OutT, bool SLICED>
 __global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
     const uint16_t* __restrict__ A, const int32_t* __restrict__ expert_offsets, int n_local, int cap_rows,
     const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1, int n_out, int K, OutT* __restrict__ C,
-    int n_col_blocks) {
+    int n_col_blocks, OutT* __restrict__ direct, int adaptive) {
   __shared__ __attribute__((aligned(1024))) uint16_t smem[kLdsBytes / 2];
-  const Unit u = find_unit(count_tiles(expert_offsets, n_local, n_col_blocks), blockIdx.x);
+  const ClassCounts cc = count_tiles(expert_offsets, n_local, n_col_blocks);
+  const Unit u = find_unit(cc, blockIdx.x);
   if (u.cls < 0) return;
+  int nk = K / BK, kt0 = 0;
+  OutT* out = C;
+  if constexpr (SLICED) {
+    int slices = gridDim.y;
+    size_t stride = (size_t)cap_rows * n_out;
+    if (adaptive) {  // the routing decides how many of the launched slices are used
+      slices = adaptive_slices(cc.n[0] + cc.n[1] + cc.n[2], nk, gridDim.y);
+      if ((int)blockIdx.y >= slices) return;
+      stride = (size_t)expert_offsets[n_local] * n_out;
+    }
+    nk /= slices;
+    kt0 = blockIdx.y * nk;
+    out = (adaptive && slices == 1) ? direct : C + blockIdx.y * stride;
+  }
   const TileCoord tc = locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx);
-  const int nk = SLICED ? K / BK / gridDim.y : K / BK, kt0 = SLICED ? blockIdx.y * nk : 0;
-  OutT* out = SLICED ? C + (size_t)blockIdx.y * cap_rows * n_out : C;
   if (u.cls == 0)
     gemm_tile<256, BN, 2, 2, 2, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out);
   else if (u.cls == 1)
@@ -350,23 +365,28 @@ __global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
     gemm_tile<64, BN, 1, 4, 4, 4, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out);
 }
 
-// Tiles a launch is expected to have: every local expert with its expected rows plus a two-sigma
-// margin (none when `exact`: one expert that takes every row), in 256-row blocks (a remainder tile
-// counts as a block).
-inline int expected_tiles(int est_rows, int n_local, int n_col_blocks, bool exact) {
-  const double avg = (double)est_rows / n_local;
-  const int blocks = (int)((avg + (exact ? 0.0 : 2.0 * sqrt(avg)) + 255.0) / 256.0);
-  return n_local * (blocks < 1 ? 1 : blocks) * n_col_blocks;
-}
-
-// K slices for a down projection whose tile count would leave most compute units idle (a single
-// shared expert with a few hundred rows: H / 256 column blocks per row block): the largest of 8, 4,
-// 2 that divides the k-tile count, keeps at least 8 k-tiles per slice and at most 256 workgroups.
-inline int k_slices_for(int est_rows, int n_local, int n_col_blocks, int K, bool exact) {
-  const int tiles = expected_tiles(est_rows, n_local, n_col_blocks, exact), nk = K / BK;
-  for (int s = 8; s >= 2; s >>= 1)
-    if (tiles * s <= 256 && nk % s == 0 && nk / s >= 8) return s;
-  return 1;
+// y[r, n] = sum over the K slices the sliced kernel used, in slice order; nothing to do when the
+// routing made it run unsliced (it wrote y itself).
+__global__ __launch_bounds__(256) void sum_adaptive_slices_kernel(const float* __restrict__ partial,
+                                                                 const int32_t* __restrict__ expert_offsets,
+                                                                 int n_local, int n_col_blocks, int nk, int max_slices,
+                                                                 int n_out, float* __restrict__ y) {
+  const ClassCounts cc = count_tiles(expert_offsets, n_local, n_col_blocks);
+  const int slices = adaptive_slices(cc.n[0] + cc.n[1] + cc.n[2], nk, max_slices);
+  if (slices == 1) return;
+  const size_t total = (size_t)expert_offsets[n_local] * n_out / 4, stride = total;
+  const float4* p = reinterpret_cast<const float4*>(partial);
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    float4 acc = p[i];
+    for (int z = 1; z < slices; ++z) {
+      const float4 v = p[z * stride + i];
+      acc.x += v.x;
+      acc.y += v.y;
+      acc.z += v.z;
+      acc.w += v.w;
+    }
+    reinterpret_cast<float4*>(y)[i] = acc;
+  }
 }
 
 }  // namespace gg

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <cmath>
+
 namespace moe {
 namespace gg {
 
@@ -105,11 +107,73 @@ __host__ __device__ inline Unit find_unit(const ClassCounts& c, int bid) {
   }
   return u;
 }
+// K slices a down projection with `n_tiles` tiles of `nk` k-tiles uses out of the `max_slices` (a
+// power of two) that were launched: as many as keep the launch within 256 workgroups with at least 8
+// k-tiles each.  Decided on the device from the actual routing, so that a shard that received far
+// fewer rows than its share still fills the chip (the cold shard of a skewed expert-parallel
+// split).  The partial sums of slice z start at row z * R of the scratch buffer, R the shard's
+// actual rows: slices * R <= slices * n_tiles * 256 / n_col_blocks <= 65536 / n_col_blocks rows.
+__host__ __device__ inline int adaptive_slices(int n_tiles, int nk, int max_slices) {
+  if (n_tiles <= 0) return 1;
+  for (int s = max_slices; s >= 2; s >>= 1)
+    if (n_tiles * s <= 256 && nk % s == 0 && nk / s >= 8) return s;
+  return 1;
+}
+// Shards with few experts and few column blocks can end up with few tiles whatever their capacity:
+// for them the slicing is adaptive.
+inline bool adaptive_slicing(int n_local, int n_col_blocks) { return n_local * n_col_blocks <= 64; }
+inline int max_k_slices(int K) {
+  const int nk = K / 64;
+  for (int s = 8; s >= 2; s >>= 1)
+    if (nk % s == 0 && nk / s >= 8) return s;
+  return 1;
+}
+inline int adaptive_scratch_rows(int cap_rows, int n_col_blocks, int max_slices) {
+  const long a = 65536 / n_col_blocks, b = (long)max_slices * cap_rows;
+  return (int)(a < b ? a : b);
+}
 // Host-side grid size covering every tile for any routing with sum_e rows_e <= cap_rows: at most
 // cap_rows/256 + n_local full row blocks, and one 128-row and one 64-row block per expert.
 inline int max_grid(int cap_rows, int n_local, int n_col_blocks) {
   const int full = (cap_rows / 256 + n_local) * n_col_blocks, small = n_local * n_col_blocks;
   return kNumXcd * ((full + kNumXcd - 1) / kNumXcd + 2 * ((small + kNumXcd - 1) / kNumXcd));
+}
+
+// Tiles a launch is expected to have: every local expert with its expected rows plus a two-sigma
+// margin (none when `exact`: one expert that takes every row), in 256-row blocks (a remainder tile
+// counts as a block).
+inline int expected_tiles(int est_rows, int n_local, int n_col_blocks, bool exact) {
+  const double avg = (double)est_rows / n_local;
+  const int blocks = (int)((avg + (exact ? 0.0 : 2.0 * sqrt(avg)) + 255.0) / 256.0);
+  return n_local * (blocks < 1 ? 1 : blocks) * n_col_blocks;
+}
+
+// K slices for a down projection whose tile count would leave most compute units idle (a single
+// shared expert with a few hundred rows: H / 256 column blocks per row block): the largest of 8, 4,
+// 2 that divides the k-tile count, keeps at least 8 k-tiles per slice and at most 256 workgroups.
+inline int k_slices_for(int est_rows, int n_local, int n_col_blocks, int K, bool exact) {
+  const int tiles = expected_tiles(est_rows, n_local, n_col_blocks, exact), nk = K / 64;
+  for (int s = 8; s >= 2; s >>= 1)
+    if (tiles * s <= 256 && nk % s == 0 && nk / s >= 8) return s;
+  return 1;
+}
+
+// How a tiled down projection is cut along K: `slices` are launched (1: unsliced); if `adaptive`
+// the kernel decides from the routing how many of them it uses (adaptive_slices), else all are used.
+// scratch_rows: rows of fp32 partial sums the launch needs room for.
+struct SlicePlan {
+  int slices;
+  bool adaptive;
+  int scratch_rows;
+};
+inline SlicePlan slice_plan(int cap_rows, int est_rows, int n_local, int n_col_blocks, int K) {
+  const bool exact = n_local == 1 && est_rows == cap_rows;  // one expert that takes every row
+  if (!exact && adaptive_slicing(n_local, n_col_blocks)) {
+    const int s = max_k_slices(K);
+    return SlicePlan{s, s > 1, s > 1 ? adaptive_scratch_rows(cap_rows, n_col_blocks, s) : 0};
+  }
+  const int s = k_slices_for(est_rows, n_local, n_col_blocks, K, exact);
+  return SlicePlan{s, false, s > 1 ? s * cap_rows : 0};
 }
 
 }  // namespace gg

@@ -45,11 +45,43 @@ def test_expert_parallel_shard_is_planned_on_its_expected_rows():
     # T = 1024, k = 2: capacity 2048 rows, of which one expert of eight expects 256
     assert B.moe_debug_ffn_plan(2048, ep8)[3] == 8          # 2 row blocks x 16 column blocks: cut along K
     assert B.moe_debug_ffn_plan(2048, full)[3] == 1
-    # buffers are still sized by the capacity
-    assert B.moe_ffn_workspace_bytes(2048, ep8) == 8 * 2048 * 4096 * 4
+    # a shard with few experts: the kernel picks the slices from the routing, and whatever it picks
+    # the partial sums fit 65536 / 16 column blocks = 4096 rows
+    assert B.moe_ffn_workspace_bytes(2048, ep8) == 4096 * 4096 * 4
+    assert B.moe_ffn_workspace_bytes(64 * 1024, ep8) == 4096 * 4096 * 4
+    assert B.moe_ffn_workspace_bytes(256, ep8) == 8 * 256 * 4096 * 4     # ... or 8 slices of the capacity
     # decode: 16 rows expected on the one local expert, but up to 128 possible: 32 rows per pass
     assert B.moe_debug_ffn_plan(128, ep8)[2] == 2
     assert B.moe_debug_ffn_plan(16, ep8)[2] == 1            # capacity itself is 16 rows
+
+
+def test_down_projection_slices_follow_the_routing_on_shards_with_few_experts():
+    import numpy as np
+    ep4 = _shard(8, 2, **MIXTRAL)        # 16 column blocks, 224 k-tiles
+    cap = 32768
+    def used(*counts):
+        return B.moe_debug_down_slices(np.concatenate([[0], np.cumsum(counts)]), cap, ep4)
+    assert used(0, 0) == 1
+    assert used(200, 100) == 8           # 2 row blocks x 16 = 32 tiles
+    assert used(300, 100) == 4           # 4 row blocks (300 = 256 + 64): 64 tiles
+    assert used(700, 700) == 2           # 8 row blocks (700 = 512 + 128 + 64): 128 tiles
+    assert used(1100, 1000) == 1         # 10 row blocks: 160 tiles, enough on their own
+    assert used(20000, 12768) == 1       # the hot shard
+    # every routing that slices fits the scratch (the call returns an error otherwise)
+    rng = np.random.default_rng(0)
+    for _ in range(2000):
+        R = int(rng.integers(0, 6000))
+        a = int(rng.integers(0, R + 1))
+        assert used(a, R - a) in (1, 2, 4, 8)
+    # a shard with many experts, or one expert that takes every row: decided on the host
+    full = _shard(8, 8, **MIXTRAL)
+    assert B.moe_debug_down_slices(np.arange(9) * 10, 8192, full) == 1
+    one = _shard(1, 1, hidden=3584, inter_full=20480, inter_slice=20480)
+    assert B.moe_debug_down_slices([0, 10], 1024, one) == 4
+    with pytest.raises(B.MoeError):
+        B.moe_debug_down_slices([0, 5, 3], cap, ep4)
+    with pytest.raises(B.MoeError):
+        B.moe_debug_down_slices([0, 5, cap + 1], cap, ep4)
 
 
 def test_k_extents_without_a_fast_streaming_kernel_go_to_the_tiled_kernel_early():

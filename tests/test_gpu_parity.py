@@ -193,6 +193,32 @@ def test_expert_ffn_against_oracle(H, I_s, counts):
     assert _rel(yb[:R], ref) < REL_L2
 
 
+@pytest.mark.parametrize("H,I_s,counts,slices", [
+    (512, 4096, [300, 10], 8),          # 3 row blocks x 2 column blocks
+    (512, 4096, [3000, 2500], 4),       # 22 x 2 tiles
+    (1024, 4096, [0, 4200], 2),         # 17 x 4 tiles, the first expert empty
+    (2048, 1024, [2500, 2100], 1),      # 19 x 8 tiles: enough on their own, written without partial sums
+    (512, 4096, [0, 0], 1),
+])
+def test_expert_ffn_on_a_shard_that_received_far_fewer_rows_than_its_capacity(H, I_s, counts, slices):
+    # a shard with two local experts of eight: how far the down projection is cut along K follows
+    # the routing, not the capacity
+    wg, wu, wd = I.make_expert_weights(0, I.MoEShape("f", H, 2, 1, I_s, True))
+    offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    R = int(offs[-1])
+    cap = 20000
+    xp = I.make_x(1, cap, H)
+    shard = B.make_shard(8, 2, 2, H, I_s, I_s)
+    assert B.moe_debug_ffn_plan(cap, shard)[:2] == (False, False)
+    assert B.moe_debug_down_slices(offs, cap, shard) == slices
+    y = _ffn_gpu(xp, offs, shard, wg, wu, wd)
+    assert np.all(np.isnan(y[R:])), "rows past R must not be written"
+    if R:
+        ref = O.expert_ffn(xp[:R], offs, wg, wu, wd)
+        assert _rel(y[:R], ref) < REL_L2
+        assert np.abs(y[:R] - ref).max() < MAX_ABS
+
+
 # ------------------------------------------------------------------ combine
 @pytest.mark.parametrize("y_bf16,out_f32", [(False, False), (False, True), (True, False)])
 @pytest.mark.parametrize("with_shared", [False, True])
