@@ -36,21 +36,31 @@ int32_t moe_debug_gemm_units(const int32_t* expert_offsets, int32_t n_local, int
  * library picks, per GEMM, a weight-streaming kernel or a tiled MFMA kernel from a cost estimate.
  * plan [4] int32 HOST: {GEMM1 streams weights (0/1), GEMM2 streams weights (0/1),
  *                       activation rows per streaming pass / 16 (1 or 2), K slices of GEMM2 (for a
- *                       tiled GEMM2 on a shard with few experts: the most the routing can select)}
+ *                       tiled GEMM2: the most the routing can select, see moe_debug_down_slices)}
  * Returns MOE_OK or MOE_ERR_INVALID_ARG.
  */
 int32_t moe_debug_ffn_plan(int32_t cap_rows, const moe_shard_t* shard, int32_t* plan);
 
+#define MOE_DEBUG_SLICE_INTS 8
+
 /*
- * K slices the tiled down projection of moe_expert_ffn uses for one routing.  An expert-parallel
- * shard's load follows the routing ("Parallelism in Inference": expert parallelism suffers from
- * load imbalance), so for shards with few experts the kernel itself decides, from expert_offsets,
- * how far a launch with few tiles is cut along K; this call runs the same decision on the host.
+ * How the tiled fp32 down projection of moe_expert_ffn is cut along K for one routing.  An
+ * expert-parallel shard's load follows the routing ("Parallelism in Inference": expert parallelism
+ * suffers from load imbalance), so the kernel itself decides, from expert_offsets, which tiles run
+ * as several K slices on otherwise idle compute units: those of the last, partial round of 256
+ * workgroups, that is the remainder tiles behind each expert's 256-row blocks and the tiles of the
+ * last 256-row blocks.  This call runs the same code on the host.
  * expert_offsets [n_local+1] int32 HOST, as for moe_debug_gemm_units.
- * Returns the number of slices (1 = unsliced) or a negative MOE_ERR_* code (MOE_ERR_WORKSPACE if
- * the partial sums would not fit what moe_ffn_workspace_bytes asks for: never, by construction).
+ * slices [4] int32 HOST: {256-row blocks (in expert order) whose tiles run whole, K slices of all
+ *                         other tiles, rows that have partial sums, rows of partial sums
+ *                         moe_ffn_workspace_bytes provides for}
+ * units  NULL, or [max_units][MOE_DEBUG_SLICE_INTS] int32 HOST, one record per workgroup:
+ *        {tile height (0 = no work), local expert, row0, column block, slice, first k-tile,
+ *         k-tiles, scratch row its row0 is written to (-1: slice 0 writes y_perm itself)}
+ * Returns the grid size, or a negative MOE_ERR_* code (MOE_ERR_WORKSPACE when max_units is too small).
  */
-int32_t moe_debug_down_slices(const int32_t* expert_offsets, int32_t cap_rows, const moe_shard_t* shard);
+int32_t moe_debug_down_slices(const int32_t* expert_offsets, int32_t cap_rows, const moe_shard_t* shard,
+                              int32_t* slices, int32_t* units, int32_t max_units);
 
 #ifdef __cplusplus
 }

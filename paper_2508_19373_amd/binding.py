@@ -31,6 +31,7 @@ DEBUG_EXPORTS = ("moe_debug_gemm_units", "moe_debug_ffn_plan", "moe_debug_down_s
 INT4_EXPORTS = ("moe_int4_dequantize", "moe_int4_quantize")
 INT4_GROUP = 64
 DEBUG_UNIT_INTS = 5
+DEBUG_SLICE_INTS = 8
 
 
 class MoeShard(ctypes.Structure):
@@ -74,7 +75,7 @@ def lib() -> ctypes.CDLL:
         L.moe_int4_quantize.restype = ctypes.c_int
         L.moe_debug_ffn_plan.argtypes = [i32, shp, vp]
         L.moe_debug_ffn_plan.restype = i32
-        L.moe_debug_down_slices.argtypes = [vp, i32, shp]
+        L.moe_debug_down_slices.argtypes = [vp, i32, shp, vp, vp, i32]
         L.moe_debug_down_slices.restype = i32
         L.moe_debug_gemm_units.argtypes = [vp, i32, i32, i32, vp, i32]
         L.moe_debug_gemm_units.restype = i32
@@ -174,17 +175,26 @@ def moe_debug_gemm_units(expert_offsets, cap_rows, n_col_blocks):
     return out[:n]
 
 
-def moe_debug_down_slices(expert_offsets, cap_rows, shard: MoeShard):
-    """Host-only: K slices the tiled down projection uses for this routing (see
-    include/moe_shard_debug.h).  `expert_offsets` is a host sequence."""
+def moe_debug_down_slices(expert_offsets, cap_rows, shard: MoeShard, with_units=False):
+    """Host-only: how the tiled fp32 down projection is cut along K for this routing (see
+    include/moe_shard_debug.h): (slices of the 256-row tiles, slices of the remainder tiles, rows
+    with partial sums, scratch rows provided), and with `with_units` also the per-workgroup records
+    [grid, DEBUG_SLICE_INTS].  `expert_offsets` is a host sequence."""
     import numpy as np
     offs = np.ascontiguousarray(expert_offsets, dtype=np.int32)
     if offs.size != shard.n_local_experts + 1:
         raise ValueError("expert_offsets must have n_local_experts + 1 entries")
-    n = lib().moe_debug_down_slices(offs.ctypes.data, cap_rows, ctypes.byref(shard))
+    info = (ctypes.c_int32 * 4)()
+    n = lib().moe_debug_down_slices(offs.ctypes.data, cap_rows, ctypes.byref(shard), info, None, 0)
     if n < 0:
         raise MoeError("moe_debug_down_slices", n)
-    return n
+    if not with_units:
+        return tuple(info)
+    out = np.zeros((n, DEBUG_SLICE_INTS), dtype=np.int32)
+    n = lib().moe_debug_down_slices(offs.ctypes.data, cap_rows, ctypes.byref(shard), info, out.ctypes.data, n)
+    if n < 0:
+        raise MoeError("moe_debug_down_slices", n)
+    return tuple(info), out[:n]
 
 
 def moe_debug_ffn_plan(cap_rows, shard: MoeShard):

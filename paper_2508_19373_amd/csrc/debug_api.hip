@@ -42,8 +42,9 @@ extern "C" int32_t moe_debug_ffn_plan(int32_t cap_rows, const moe_shard_t* shard
   return MOE_OK;
 }
 
-extern "C" int32_t moe_debug_down_slices(const int32_t* expert_offsets, int32_t cap_rows, const moe_shard_t* shard) {
-  if (expert_offsets == nullptr || cap_rows < 0 || shard == nullptr) return MOE_ERR_INVALID_ARG;
+extern "C" int32_t moe_debug_down_slices(const int32_t* expert_offsets, int32_t cap_rows, const moe_shard_t* shard,
+                                         int32_t* slices, int32_t* units, int32_t max_units) {
+  if (expert_offsets == nullptr || cap_rows < 0 || shard == nullptr || slices == nullptr) return MOE_ERR_INVALID_ARG;
   if (shard->n_experts < 1 || shard->n_local_experts < 1 || shard->n_local_experts > shard->n_experts ||
       shard->hidden < 64 || shard->inter_slice < 64)
     return MOE_ERR_INVALID_ARG;
@@ -52,12 +53,36 @@ extern "C" int32_t moe_debug_down_slices(const int32_t* expert_offsets, int32_t 
     if (expert_offsets[e] > expert_offsets[e + 1]) return MOE_ERR_INVALID_ARG;
   if (expert_offsets[0] < 0 || expert_offsets[n_local] > cap_rows) return MOE_ERR_INVALID_ARG;
   using namespace moe::gg;
-  const int ncb = (shard->hidden + 255) / 256;
-  const SlicePlan sp =
-      slice_plan(cap_rows, moe::expected_rows(cap_rows, shard), n_local, ncb, shard->inter_slice);
-  if (!sp.adaptive) return sp.slices;
+  const int ncb = (shard->hidden + 255) / 256, nk = shard->inter_slice / 64;
+  const SlicePlan sp = slice_plan(cap_rows, ncb, shard->inter_slice);
   const ClassCounts cc = count_tiles(expert_offsets, n_local, ncb);
-  const int used = adaptive_slices(cc.n[0] + cc.n[1] + cc.n[2], shard->inter_slice / 64, sp.slices);
-  if ((long)used * expert_offsets[n_local] > sp.scratch_rows && used > 1) return MOE_ERR_WORKSPACE;
-  return used;
+  const SliceChoice sc = choose_slices(cc, ncb, nk, sp.max_slices);
+  slices[0] = sc.keep_rb;
+  slices[1] = sc.slices;
+  slices[2] = sc.slices > 1 ? sliced_rows(expert_offsets, n_local, 0, sc.keep_rb).total : 0;
+  slices[3] = sp.scratch_rows;
+  const int grid = sp.max_slices > 1 ? sliced_grid(cap_rows, n_local, ncb) : max_grid(cap_rows, n_local, ncb);
+  if (units == nullptr) return grid;
+  if (grid > max_units) return MOE_ERR_WORKSPACE;
+  for (int b = 0; b < grid; ++b) {
+    int32_t* rec = units + (size_t)b * MOE_DEBUG_SLICE_INTS;
+    for (int i = 0; i < MOE_DEBUG_SLICE_INTS; ++i) rec[i] = 0;
+    const SlicedUnit u = find_sliced_unit(cc, sc, ncb, b);
+    if (u.cls < 0) continue;
+    const TileCoord tc = (u.cls == 3 || u.cls == 0)
+                             ? locate_full_tile(expert_offsets, n_local, ncb, sc.keep_rb, u.cls == 0, u.idx)
+                             : locate_tile(expert_offsets, n_local, ncb, u.cls, u.idx);
+    const int s = u.cls == 3 ? 1 : sc.slices;
+    const int kt0 = u.z * nk / s;
+    const SlicedRows sr = sliced_rows(expert_offsets, n_local, tc.expert, sc.keep_rb);
+    rec[0] = (u.cls == 3 || u.cls == 0) ? 256 : (u.cls == 1 ? 128 : 64);
+    rec[1] = tc.expert;
+    rec[2] = tc.row0;
+    rec[3] = tc.nb;
+    rec[4] = u.z;
+    rec[5] = kt0;
+    rec[6] = (u.z + 1) * nk / s - kt0;
+    rec[7] = u.z == 0 ? -1 : (u.z - 1) * sr.total + sr.base + tc.row0 - sr.first;
+  }
+  return grid;
 }

@@ -49,30 +49,23 @@ hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, i
                        static_cast<uint16_t*>(nullptr), 0);
     return hipGetLastError();
   }
-  const gg::SlicePlan sp = workspace == nullptr ? gg::SlicePlan{1, false, 0}
-                                                : gg::slice_plan(cap_rows, est_rows, n_local, ncb, I_s);
-  dim3 grid = grid_for(ncb);
-  grid.y = sp.slices;
+  const gg::SlicePlan sp = workspace == nullptr ? gg::SlicePlan{1, 0} : gg::slice_plan(cap_rows, ncb, I_s);
   float* yp = static_cast<float*>(y_perm);
   float* ws = static_cast<float*>(workspace);
   const uint16_t* wd = static_cast<const uint16_t*>(w_down);
-  if (sp.slices == 1) {
-    hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, float, false>), grid, block, 0, stream, hw,
+  if (sp.max_slices == 1) {
+    hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, float, false>), grid_for(ncb), block, 0, stream, hw,
                        expert_offsets, n_local, cap_rows, wd, static_cast<const uint16_t*>(nullptr), H, I_s, yp, ncb,
                        static_cast<float*>(nullptr), 0);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, float, true>), grid, block, 0, stream, hw,
-                     expert_offsets, n_local, cap_rows, wd, static_cast<const uint16_t*>(nullptr), H, I_s, ws, ncb, yp,
-                     sp.adaptive ? 1 : 0);
+  hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, float, true>),
+                     dim3(gg::sliced_grid(cap_rows, n_local, ncb)), block, 0, stream, hw, expert_offsets, n_local,
+                     cap_rows, wd, static_cast<const uint16_t*>(nullptr), H, I_s, ws, ncb, yp, sp.max_slices);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
-  if (sp.adaptive)
-    hipLaunchKernelGGL(gg::sum_adaptive_slices_kernel, dim3(256), dim3(256), 0, stream, ws, expert_offsets, n_local,
-                       ncb, I_s / gg::BK, sp.slices, H, yp);
-  else
-    hipLaunchKernelGGL(gw::sum_slices_kernel, dim3(256), dim3(256), 0, stream, ws, expert_offsets, n_local, cap_rows,
-                       H, sp.slices, yp);
+  hipLaunchKernelGGL(gg::sum_sliced_kernel, dim3(1024), dim3(256), 0, stream, ws, expert_offsets, n_local, ncb,
+                     I_s / gg::BK, sp.max_slices, H, yp);
   return hipGetLastError();
 }
 
@@ -219,8 +212,7 @@ size_t ffn_workspace_bytes(int cap_rows, int est_rows, int n_local, int H, int I
     const gw::WalkPlan p2 = gw::plan_for(I_s, decode_mt(cap_rows, est_rows, n_local));
     slices = p2.nw == 0 ? 1 : p2.slices;
   } else {
-    const gg::SlicePlan sp = gg::slice_plan(cap_rows, est_rows, n_local, (H + 255) / 256, I_s);
-    return (size_t)sp.scratch_rows * H * sizeof(float);
+    return (size_t)gg::slice_plan(cap_rows, (H + 255) / 256, I_s).scratch_rows * H * sizeof(float);
   }
   return slices > 1 ? (size_t)slices * cap_rows * H * sizeof(float) : 0;
 }
@@ -236,7 +228,7 @@ void ffn_plan(int cap_rows, int est_rows, int n_local, int H, int I_s, int32_t o
     const gw::WalkPlan p2 = gw::plan_for(I_s, mt);
     out[3] = p2.nw == 0 ? 1 : p2.slices;
   } else {
-    out[3] = gg::slice_plan(cap_rows, est_rows, n_local, (H + 255) / 256, I_s).slices;
+    out[3] = gg::slice_plan(cap_rows, (H + 255) / 256, I_s).max_slices;
   }
 }
 

@@ -326,66 +326,89 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
 }
 
 // Kernel: 256 threads (4 wavefronts); each workgroup computes one tile, whose height class
-// selects the wave arrangement and the LDS stage counts.  SLICED: grid.y = K slices, slice z covers
-// k-tiles [z, z+1) * K / 64 / gridDim.y and writes its partial sums to C + z * cap_rows * n_out (a
-// launch whose tiles would fill less than half the compute units is cut along K; the caller adds
-// the slices in order).  With `adaptive` the number of slices actually used follows the routing
-// (adaptive_slices on the real tile count): partial sums then go to C + z * R * n_out, R the
-// shard's actual rows, and an unsliced run writes `direct`.  A separate instantiation, so that the unsliced kernels keep
-// their register allocation (the extra live values cost the main path 2-3 %).
+// selects the wave arrangement and the LDS stage counts.  SLICED (fp32 down projection): tiles may
+// be cut along K as choose_slices decides from the routing; slice 0 of a tile writes `y`, slice
+// z >= 1 its partial sums into `C` (see sliced_rows), which sum_sliced_kernel adds to y.  A separate
+// instantiation, so that the unsliced kernels keep their register allocation.
 template <int BN, bool GATEUP, typename OutT, bool SLICED>
 __global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
     const uint16_t* __restrict__ A, const int32_t* __restrict__ expert_offsets, int n_local, int cap_rows,
     const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1, int n_out, int K, OutT* __restrict__ C,
-    int n_col_blocks, OutT* __restrict__ direct, int adaptive) {
+    int n_col_blocks, OutT* __restrict__ y, int max_slices) {
   __shared__ __attribute__((aligned(1024))) uint16_t smem[kLdsBytes / 2];
   const ClassCounts cc = count_tiles(expert_offsets, n_local, n_col_blocks);
-  const Unit u = find_unit(cc, blockIdx.x);
-  if (u.cls < 0) return;
-  int nk = K / BK, kt0 = 0;
+  int nk = K / BK, kt0 = 0, cls;
   OutT* out = C;
+  TileCoord tc;
   if constexpr (SLICED) {
-    int slices = gridDim.y;
-    size_t stride = (size_t)cap_rows * n_out;
-    if (adaptive) {  // the routing decides how many of the launched slices are used
-      slices = adaptive_slices(cc.n[0] + cc.n[1] + cc.n[2], nk, gridDim.y);
-      if ((int)blockIdx.y >= slices) return;
-      stride = (size_t)expert_offsets[n_local] * n_out;
+    const SliceChoice sc = choose_slices(cc, n_col_blocks, nk, max_slices);
+    const SlicedUnit u = find_sliced_unit(cc, sc, n_col_blocks, blockIdx.x);
+    if (u.cls < 0) return;
+    cls = u.cls == 3 ? 0 : u.cls;
+    tc = (u.cls == 3 || u.cls == 0)
+             ? locate_full_tile(expert_offsets, n_local, n_col_blocks, sc.keep_rb, u.cls == 0, u.idx)
+             : locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx);
+    out = y;
+    if (u.cls != 3) {
+      kt0 = u.z * nk / sc.slices;
+      nk = (u.z + 1) * nk / sc.slices - kt0;
+      if (u.z > 0) {
+        const SlicedRows sr = sliced_rows(expert_offsets, n_local, tc.expert, sc.keep_rb);
+        out = C + ((ptrdiff_t)(u.z - 1) * sr.total + sr.base - sr.first) * n_out;
+      }
     }
-    nk /= slices;
-    kt0 = blockIdx.y * nk;
-    out = (adaptive && slices == 1) ? direct : C + blockIdx.y * stride;
+  } else {
+    const Unit u = find_unit(cc, blockIdx.x);
+    if (u.cls < 0) return;
+    cls = u.cls;
+    tc = locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx);
   }
-  const TileCoord tc = locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx);
-  if (u.cls == 0)
+  if (cls == 0)
     gemm_tile<256, BN, 2, 2, 2, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out);
-  else if (u.cls == 1)
+  else if (cls == 1)
     gemm_tile<128, BN, 2, 2, 3, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out);
   else
     gemm_tile<64, BN, 1, 4, 4, 4, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out);
 }
 
-// y[r, n] = sum over the K slices the sliced kernel used, in slice order; nothing to do when the
-// routing made it run unsliced (it wrote y itself).
-__global__ __launch_bounds__(256) void sum_adaptive_slices_kernel(const float* __restrict__ partial,
-                                                                 const int32_t* __restrict__ expert_offsets,
-                                                                 int n_local, int n_col_blocks, int nk, int max_slices,
-                                                                 int n_out, float* __restrict__ y) {
+// y[r, :] += partial sums of slices 1, 2, ... in that order, for the rows the sliced kernel cut
+// along K (it repeats that kernel's decision).  One workgroup per row.
+__global__ __launch_bounds__(256) void sum_sliced_kernel(const float* __restrict__ partial,
+                                                        const int32_t* __restrict__ expert_offsets, int n_local,
+                                                        int n_col_blocks, int nk, int max_slices, int n_out,
+                                                        float* __restrict__ y) {
   const ClassCounts cc = count_tiles(expert_offsets, n_local, n_col_blocks);
-  const int slices = adaptive_slices(cc.n[0] + cc.n[1] + cc.n[2], nk, max_slices);
-  if (slices == 1) return;
-  const size_t total = (size_t)expert_offsets[n_local] * n_out / 4, stride = total;
+  const SliceChoice sc = choose_slices(cc, n_col_blocks, nk, max_slices);
+  if (sc.slices == 1) return;
+  const int total = sliced_rows(expert_offsets, n_local, 0, sc.keep_rb).total;
+  const size_t stride = (size_t)total * n_out / 4;
   const float4* p = reinterpret_cast<const float4*>(partial);
-  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-    float4 acc = p[i];
-    for (int z = 1; z < slices; ++z) {
-      const float4 v = p[z * stride + i];
-      acc.x += v.x;
-      acc.y += v.y;
-      acc.z += v.z;
-      acc.w += v.w;
+  for (int i = blockIdx.x; i < total; i += gridDim.x) {
+    int row = 0, base = 0, before = 0;
+    for (int e = 0; e < n_local; ++e) {
+      const int lo = expert_offsets[e], hi = expert_offsets[e + 1];
+      const int n256 = row_blocks(hi - lo).n256;
+      const int first = min(hi, lo + min(max(sc.keep_rb - before, 0), n256) * 256);
+      if (i < base + hi - first) {
+        row = first + i - base;
+        break;
+      }
+      base += hi - first;
+      before += n256;
     }
-    reinterpret_cast<float4*>(y)[i] = acc;
+    float4* yr = reinterpret_cast<float4*>(y + (size_t)row * n_out);
+    const float4* pr = p + (size_t)i * n_out / 4;
+    for (int c = threadIdx.x; c < n_out / 4; c += blockDim.x) {
+      float4 acc = yr[c];
+      for (int z = 1; z < sc.slices; ++z) {
+        const float4 v = pr[(z - 1) * stride + c];
+        acc.x += v.x;
+        acc.y += v.y;
+        acc.z += v.z;
+        acc.w += v.w;
+      }
+      yr[c] = acc;
+    }
   }
 }
 

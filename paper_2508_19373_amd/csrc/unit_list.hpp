@@ -107,29 +107,131 @@ __host__ __device__ inline Unit find_unit(const ClassCounts& c, int bid) {
   }
   return u;
 }
-// K slices a down projection with `n_tiles` tiles of `nk` k-tiles uses out of the `max_slices` (a
-// power of two) that were launched: as many as keep the launch within 256 workgroups with at least 8
-// k-tiles each.  Decided on the device from the actual routing, so that a shard that received far
-// fewer rows than its share still fills the chip (the cold shard of a skewed expert-parallel
-// split).  The partial sums of slice z start at row z * R of the scratch buffer, R the shard's
-// actual rows: slices * R <= slices * n_tiles * 256 / n_col_blocks <= 65536 / n_col_blocks rows.
-__host__ __device__ inline int adaptive_slices(int n_tiles, int nk, int max_slices) {
+// ---- K slices of the fp32 down projection, decided from the routing -------------------------------
+// One workgroup per tile leaves compute units idle for a whole walk over K whenever the tiles do
+// not fill a round of 256: a launch with few tiles (a single shared expert, the cold shard of a
+// skewed expert-parallel split), the last round of the 256-row tiles (544 tiles are 2.1 rounds and
+// take 3), and the remainder phase, where the last, at most 192, rows of every expert are 128- and
+// 64-row tiles that re-stream the expert's weights latency-bound.  The tiles of that last round are
+// therefore cut along K into slices that run as separate workgroups: the remainder tiles and the
+// 256-row tiles of the last row blocks (in expert order), as many whole row blocks as the last
+// round holds.  Slice 0 writes y, slice z >= 1 writes fp32 partial sums that a second kernel adds
+// to y in slice order.
+//
+// fit_slices: as many slices as keep `n_tiles` tiles within 256 workgroups, at most `max_slices`,
+// at least 8 k-tiles each.
+__host__ __device__ inline int fit_slices(int n_tiles, int nk, int max_slices) {
   if (n_tiles <= 0) return 1;
-  for (int s = max_slices; s >= 2; s >>= 1)
-    if (n_tiles * s <= 256 && nk % s == 0 && nk / s >= 8) return s;
-  return 1;
+  int s = 256 / n_tiles;
+  if (s > max_slices) s = max_slices;
+  if (s > nk / 8) s = nk / 8;
+  return s < 1 ? 1 : s;
 }
-// Shards with few experts and few column blocks can end up with few tiles whatever their capacity:
-// for them the slicing is adaptive.
-inline bool adaptive_slicing(int n_local, int n_col_blocks) { return n_local * n_col_blocks <= 64; }
+// keep_rb: 256-row blocks (counted over the experts in order) whose tiles run whole; the tiles of
+// all later 256-row blocks and all remainder tiles run in `slices` K slices.
+struct SliceChoice {
+  int keep_rb, slices;
+};
+__host__ __device__ inline SliceChoice choose_slices(const ClassCounts& c, int n_col_blocks, int nk,
+                                                     int max_slices) {
+  const int n_rb = c.n[0] / n_col_blocks, n_small = c.n[1] + c.n[2];
+  int tail_rb = 0;
+  if (c.n[0] + n_small <= 128) {
+    tail_rb = n_rb;  // less than half a round in all
+  } else {
+    const int last = c.n[0] % 256;  // 256-row tiles in the last, partial round
+    if (last > 0 && last <= 128) tail_rb = (last + n_col_blocks - 1) / n_col_blocks;
+  }
+  SliceChoice sc;
+  sc.slices = fit_slices(tail_rb * n_col_blocks + n_small, nk, max_slices);
+  if (sc.slices == 1 && n_small > 0) sc.slices = fit_slices(n_small, nk, max_slices), tail_rb = 0;
+  sc.keep_rb = sc.slices > 1 ? n_rb - tail_rb : n_rb;
+  return sc;
+}
 inline int max_k_slices(int K) {
-  const int nk = K / 64;
-  for (int s = 8; s >= 2; s >>= 1)
-    if (nk % s == 0 && nk / s >= 8) return s;
-  return 1;
+  const int s = K / 64 / 8;
+  return s > 8 ? 8 : (s < 1 ? 1 : s);
 }
-inline int adaptive_scratch_rows(int cap_rows, int n_col_blocks, int max_slices) {
-  const long a = 65536 / n_col_blocks, b = (long)max_slices * cap_rows;
+// Workgroup -> (tile, slice).  Order: the whole 256-row tiles as in find_unit; then the sliced
+// 256-row tiles, the 128-row and the 64-row tiles, each list repeated once per slice, all tiles of
+// slice 0 first (tiles of one slice walk the same k range, so they share weight panels).
+struct SlicedUnit {
+  int cls, idx, z;  // cls: 0/1/2 height class, 3 = whole 256-row tile (z = 0)
+};
+__host__ __device__ inline SlicedUnit find_sliced_unit(const ClassCounts& c, const SliceChoice& sc, int n_col_blocks,
+                                                       int bid) {
+  const int kept = sc.keep_rb * n_col_blocks;
+  const int n[4] = {kept, c.n[0] - kept, c.n[1], c.n[2]};
+  SlicedUnit r = {-1, 0, 0};
+  const int xcd = bid % kNumXcd;
+  int slot = bid / kNumXcd;
+  for (int v = 0; v < 4; ++v) {
+    const int m = v == 0 ? n[0] : n[v] * sc.slices;
+    const int chunk = (m + kNumXcd - 1) / kNumXcd;
+    if (slot < chunk) {
+      const int i = xcd * chunk + slot;
+      if (i < m) {
+        r.cls = v == 0 ? 3 : v - 1;
+        r.z = i / n[v];
+        r.idx = i % n[v];
+      }
+      return r;
+    }
+    slot -= chunk;
+  }
+  return r;
+}
+// 256-row tile `idx` among the whole ones (tail = false) or among the sliced ones (tail = true):
+// experts in order, column blocks, row blocks fastest, as locate_tile.
+__host__ __device__ inline TileCoord locate_full_tile(const int32_t* __restrict__ expert_offsets, int n_local,
+                                                      int n_col_blocks, int keep_rb, bool tail, int idx) {
+  TileCoord t = {0, 0, 0, 0};
+  int before = 0;
+  for (int e = 0; e < n_local; ++e) {
+    const int lo = expert_offsets[e], hi = expert_offsets[e + 1];
+    const int n256 = row_blocks(hi - lo).n256;
+    const int kept = min(max(keep_rb - before, 0), n256);
+    const int mbs = tail ? n256 - kept : kept;
+    const int tiles = mbs * n_col_blocks;
+    if (idx < tiles) {
+      t.expert = e;
+      t.nb = idx / mbs;
+      t.row_end = hi;
+      t.row0 = lo + (idx % mbs + (tail ? kept : 0)) * 256;
+      return t;
+    }
+    idx -= tiles;
+    before += n256;
+  }
+  return t;
+}
+// Rows that have partial sums, numbered compactly over the experts: each expert's rows behind its
+// whole 256-row blocks.  For expert e: `first` is its first such row and `base` that row's compact
+// number; `total` counts them over the shard.  Slice z >= 1 keeps the partial sums of compact row i
+// at row (z - 1) * total + i of the scratch: (slices - 1) * total <= 65536 / n_col_blocks rows,
+// since slices * tiles <= 256 and a tile has at most 256 rows.
+struct SlicedRows {
+  int base, first, total;
+};
+__host__ __device__ inline SlicedRows sliced_rows(const int32_t* __restrict__ expert_offsets, int n_local, int e,
+                                                  int keep_rb) {
+  SlicedRows r = {0, 0, 0};
+  int before = 0;
+  for (int i = 0; i < n_local; ++i) {
+    const int lo = expert_offsets[i], hi = expert_offsets[i + 1];
+    const int n256 = row_blocks(hi - lo).n256;
+    const int first = min(hi, lo + min(max(keep_rb - before, 0), n256) * 256);
+    if (i == e) {
+      r.base = r.total;
+      r.first = first;
+    }
+    r.total += hi - first;
+    before += n256;
+  }
+  return r;
+}
+inline int sliced_scratch_rows(int cap_rows, int n_col_blocks, int max_slices) {
+  const long a = 65536 / n_col_blocks, b = (long)(max_slices - 1) * cap_rows;
   return (int)(a < b ? a : b);
 }
 // Host-side grid size covering every tile for any routing with sum_e rows_e <= cap_rows: at most
@@ -137,6 +239,14 @@ inline int adaptive_scratch_rows(int cap_rows, int n_col_blocks, int max_slices)
 inline int max_grid(int cap_rows, int n_local, int n_col_blocks) {
   const int full = (cap_rows / 256 + n_local) * n_col_blocks, small = n_local * n_col_blocks;
   return kNumXcd * ((full + kNumXcd - 1) / kNumXcd + 2 * ((small + kNumXcd - 1) / kNumXcd));
+}
+
+// Grid of the sliced kernel: the whole tiles, and three lists that have at most 256 workgroups
+// each when they are cut along K.
+inline int sliced_grid(int cap_rows, int n_local, int n_col_blocks) {
+  int full = (cap_rows / 256 + n_local) * n_col_blocks, small = n_local * n_col_blocks;
+  if (small < 256) small = 256;
+  return kNumXcd * ((full + kNumXcd - 1) / kNumXcd + 256 / kNumXcd + 2 * ((small + kNumXcd - 1) / kNumXcd));
 }
 
 // Tiles a launch is expected to have: every local expert with its expected rows plus a two-sigma
@@ -158,22 +268,14 @@ inline int k_slices_for(int est_rows, int n_local, int n_col_blocks, int K, bool
   return 1;
 }
 
-// How a tiled down projection is cut along K: `slices` are launched (1: unsliced); if `adaptive`
-// the kernel decides from the routing how many of them it uses (adaptive_slices), else all are used.
-// scratch_rows: rows of fp32 partial sums the launch needs room for.
+// How a tiled fp32 down projection may be cut along K: up to `max_slices` (1: never), chosen per
+// routing on the device (choose_slices); scratch_rows: rows of fp32 partial sums it needs room for.
 struct SlicePlan {
-  int slices;
-  bool adaptive;
-  int scratch_rows;
+  int max_slices, scratch_rows;
 };
-inline SlicePlan slice_plan(int cap_rows, int est_rows, int n_local, int n_col_blocks, int K) {
-  const bool exact = n_local == 1 && est_rows == cap_rows;  // one expert that takes every row
-  if (!exact && adaptive_slicing(n_local, n_col_blocks)) {
-    const int s = max_k_slices(K);
-    return SlicePlan{s, s > 1, s > 1 ? adaptive_scratch_rows(cap_rows, n_col_blocks, s) : 0};
-  }
-  const int s = k_slices_for(est_rows, n_local, n_col_blocks, K, exact);
-  return SlicePlan{s, false, s > 1 ? s * cap_rows : 0};
+inline SlicePlan slice_plan(int cap_rows, int n_col_blocks, int K) {
+  const int s = max_k_slices(K);
+  return SlicePlan{s, s > 1 ? sliced_scratch_rows(cap_rows, n_col_blocks, s) : 0};
 }
 
 }  // namespace gg

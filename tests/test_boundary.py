@@ -137,14 +137,16 @@ def test_expert_ffn_validation(lib):
     assert f(P, P, 8, ctypes.byref(_shard(inter_full=1000, inter_slice=500)), P, P, P, P, P, P, W, 0, None) \
         == B.MOE_ERR_UNSUPPORTED_SHAPE
     assert f(P, P, 8, ctypes.byref(s), P, P, P + 8, P, P, P, W, 0, None) == B.MOE_ERR_INVALID_ARG
-    # decode-sized call on a Mixtral-shaped shard needs split-K scratch; a prefill-sized one does not
+    # decode-sized call on a Mixtral-shaped shard needs split-K scratch; a prefill-sized one room for the
+    # partial sums of tiles cut along K (65536 / 16 column blocks rows, whatever the capacity)
     mix = _shard(hidden=4096, inter_full=14336, inter_slice=14336)
     need = B.moe_ffn_workspace_bytes(32, mix)
     assert need == 2 * 32 * 4096 * 4   # 16 wavefronts x 14 k-steps x 2 K slices
-    assert B.moe_ffn_workspace_bytes(8192, mix) == 0
+    assert B.moe_ffn_workspace_bytes(8192, mix) == 4096 * 4096 * 4
+    assert B.moe_ffn_workspace_bytes(8192, _shard(hidden=4096, inter_full=512, inter_slice=512)) == 0   # K too short to cut
     # a single expert with a few hundred rows: the tiled down projection is cut along K
     one = _shard(n_experts=1, n_local_experts=1, hidden=3584, inter_full=20480, inter_slice=20480)
-    assert B.moe_ffn_workspace_bytes(1024, one) == 4 * 1024 * 3584 * 4   # 4 row blocks x 14 column blocks x 4 slices
+    assert B.moe_ffn_workspace_bytes(1024, one) == (65536 // 14) * 3584 * 4   # up to 8 slices, 7 of them in scratch
     assert f(P, P, 32, ctypes.byref(mix), P, P, P, P, P, None, 0, 0, None) == B.MOE_ERR_WORKSPACE
     assert f(P, P, 32, ctypes.byref(mix), P, P, P, P, P, P, need - 1, 0, None) == B.MOE_ERR_WORKSPACE
 

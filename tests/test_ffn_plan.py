@@ -23,9 +23,9 @@ def test_routed_experts_switch_regime_near_twenty_rows_per_expert():
     # up to 16 rows expected in the fullest expert: 16 rows per pass, 16 wavefronts, K = 14336 in 2 slices
     assert B.moe_debug_ffn_plan(32, s) == (True, True, 1, 2)
     assert B.moe_debug_ffn_plan(128, s)[2] == 2
-    # the headline prefill shape: tiled kernels, no K slices, no scratch
-    assert B.moe_debug_ffn_plan(8192, s) == (False, False, 2, 1)
-    assert B.moe_ffn_workspace_bytes(8192, s) == 0
+    # the headline prefill shape: tiled kernels; K slices for the remainder tiles only (see below)
+    assert B.moe_debug_ffn_plan(8192, s) == (False, False, 2, 8)
+    assert B.moe_ffn_workspace_bytes(8192, s) == 4096 * 4096 * 4
 
 
 def test_single_shared_expert_never_runs_its_down_projection_on_a_handful_of_tiles():
@@ -35,53 +35,122 @@ def test_single_shared_expert_never_runs_its_down_projection_on_a_handful_of_til
         w1, w2, mt, slices = B.moe_debug_ffn_plan(rows, s)
         assert not w1 and not w2 and slices >= 2, rows
     assert B.moe_debug_ffn_plan(256, s) == (False, False, 2, 8)
-    assert B.moe_debug_ffn_plan(4096, s) == (False, False, 2, 1)          # enough tiles on their own
-    assert B.moe_ffn_workspace_bytes(256, s) == 8 * 256 * 3584 * 4
+    assert B.moe_debug_down_slices([0, 256], 256, s)[:2] == (0, 8)        # 14 tiles, each in 8 slices
+    assert B.moe_debug_down_slices([0, 1024], 1024, s)[:2] == (0, 4)      # 56 tiles
+    assert B.moe_debug_down_slices([0, 4096], 4096, s)[:2] == (16, 1)     # 224 tiles: enough on their own
+    assert B.moe_ffn_workspace_bytes(256, s) == 7 * 256 * 3584 * 4
+    assert B.moe_ffn_workspace_bytes(4096, s) == (65536 // 14) * 3584 * 4
 
 
 def test_expert_parallel_shard_is_planned_on_its_expected_rows():
     full = _shard(8, 8, **MIXTRAL)
     ep8 = _shard(8, 1, **MIXTRAL)
-    # T = 1024, k = 2: capacity 2048 rows, of which one expert of eight expects 256
-    assert B.moe_debug_ffn_plan(2048, ep8)[3] == 8          # 2 row blocks x 16 column blocks: cut along K
-    assert B.moe_debug_ffn_plan(2048, full)[3] == 1
-    # a shard with few experts: the kernel picks the slices from the routing, and whatever it picks
-    # the partial sums fit 65536 / 16 column blocks = 4096 rows
-    assert B.moe_ffn_workspace_bytes(2048, ep8) == 4096 * 4096 * 4
-    assert B.moe_ffn_workspace_bytes(64 * 1024, ep8) == 4096 * 4096 * 4
-    assert B.moe_ffn_workspace_bytes(256, ep8) == 8 * 256 * 4096 * 4     # ... or 8 slices of the capacity
+    # T = 1024, k = 2: capacity 2048 rows, of which one expert of eight expects 256: tiled kernels
+    assert B.moe_debug_ffn_plan(2048, ep8)[:2] == (False, False)
+    assert B.moe_debug_ffn_plan(2048, full)[:2] == (False, False)
     # decode: 16 rows expected on the one local expert, but up to 128 possible: 32 rows per pass
     assert B.moe_debug_ffn_plan(128, ep8)[2] == 2
     assert B.moe_debug_ffn_plan(16, ep8)[2] == 1            # capacity itself is 16 rows
 
 
-def test_down_projection_slices_follow_the_routing_on_shards_with_few_experts():
+def _offsets(counts):
     import numpy as np
+    return np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+
+
+def test_down_projection_slices_follow_the_routing():
     ep4 = _shard(8, 2, **MIXTRAL)        # 16 column blocks, 224 k-tiles
     cap = 32768
     def used(*counts):
-        return B.moe_debug_down_slices(np.concatenate([[0], np.cumsum(counts)]), cap, ep4)
-    assert used(0, 0) == 1
-    assert used(200, 100) == 8           # 2 row blocks x 16 = 32 tiles
-    assert used(300, 100) == 4           # 4 row blocks (300 = 256 + 64): 64 tiles
-    assert used(700, 700) == 2           # 8 row blocks (700 = 512 + 128 + 64): 128 tiles
-    assert used(1100, 1000) == 1         # 10 row blocks: 160 tiles, enough on their own
-    assert used(20000, 12768) == 1       # the hot shard
-    # every routing that slices fits the scratch (the call returns an error otherwise)
-    rng = np.random.default_rng(0)
-    for _ in range(2000):
-        R = int(rng.integers(0, 6000))
-        a = int(rng.integers(0, R + 1))
-        assert used(a, R - a) in (1, 2, 4, 8)
-    # a shard with many experts, or one expert that takes every row: decided on the host
+        return B.moe_debug_down_slices(_offsets(counts), cap, ep4)[:2]    # (row blocks run whole, slices of the rest)
+    assert used(0, 0) == (0, 1)
+    assert used(200, 100) == (0, 8)      # 2 row blocks x 16 = 32 tiles: every tile in 8 slices
+    assert used(300, 100) == (0, 5)      # 3 row blocks (256 + 64, 128): 48 tiles
+    assert used(700, 0) == (0, 4)        # 512 + 128 + 64
+    assert used(700, 700) == (0, 2)      # 128 tiles
+    assert used(1100, 1000) == (8, 8)    # 8 whole row blocks (128 tiles), the 128-row remainder in 8 slices
+    assert used(1024, 512) == (0, 2) and used(10240, 5120) == (60, 1)    # no remainder tiles; 960 tiles = 3.75 rounds
+    # the hot shard: 78 + 50 row blocks = 2048 tiles = 8 rounds exactly; the remainder tiles in 8 slices
+    assert used(20000, 12768) == (128, 8)
+    # 33 row blocks = 528 tiles = 2.06 rounds: the last row block (16 tiles) and the 64 remainder tiles in 3 slices
+    assert used(5000, 3770) == (32, 3)
+    assert used(5120, 3584) == (32, 8)   # 34 row blocks, no remainders: the last two in 8 slices
+    # the scratch is sized for any routing: 65536 / 16 rows, or 7 slices of the capacity
+    assert B.moe_ffn_workspace_bytes(cap, ep4) == 4096 * 4096 * 4
+    # the unsharded layer: 31 row blocks = 496 tiles, 240 in the last round: only the remainder tiles are cut
     full = _shard(8, 8, **MIXTRAL)
-    assert B.moe_debug_down_slices(np.arange(9) * 10, 8192, full) == 1
-    one = _shard(1, 1, hidden=3584, inter_full=20480, inter_slice=20480)
-    assert B.moe_debug_down_slices([0, 10], 1024, one) == 4
+    counts = (1030, 1000, 1100, 1024, 960, 1090, 1020, 968)
+    info = B.moe_debug_down_slices(_offsets(counts), 8192, full)
+    assert info[:2] == (31, 3)           # 5 remainder row blocks x 16 column blocks
+    assert info[2] == sum(c % 256 for c in counts if c % 256 <= 192) and info[3] == 4096
     with pytest.raises(B.MoeError):
         B.moe_debug_down_slices([0, 5, 3], cap, ep4)
     with pytest.raises(B.MoeError):
         B.moe_debug_down_slices([0, 5, cap + 1], cap, ep4)
+
+
+@pytest.mark.parametrize("E_loc,hidden,inter,cap,max_rows", [
+    (2, 4096, 14336, 32768, 3000), (2, 4096, 14336, 32768, 30000), (8, 4096, 14336, 8192, 8192),
+    (1, 3584, 20480, 4096, 4096), (4, 512, 1024, 3000, 3000), (60, 2048, 1408, 16384, 16384),
+    (16, 3584, 2560, 6000, 2000), (3, 256, 640, 900, 900), (5, 2048, 2048, 9000, 9000),
+])
+def test_sliced_work_list_covers_every_tile_and_slice_once(E_loc, hidden, inter, cap, max_rows):
+    import numpy as np
+    rng = np.random.default_rng(E_loc * 1000 + hidden)
+    shard = _shard(E_loc, E_loc, hidden=hidden, inter_full=inter, inter_slice=inter)
+    ncb, nk = (hidden + 255) // 256, inter // 64
+    n_sliced_cases = 0
+    for trial in range(40):
+        R = int(rng.integers(0, max_rows + 1))
+        cuts = np.sort(rng.integers(0, R + 1, size=E_loc - 1))
+        counts = np.diff(np.concatenate([[0], cuts, [R]]))
+        if trial % 5 == 0:
+            counts = (counts // 256) * 256          # no remainder tiles
+        offs = _offsets(counts)
+        (keep_rb, slices, rows, scratch), units = B.moe_debug_down_slices(offs, cap, shard, with_units=True)
+        plain = B.moe_debug_gemm_units(offs, cap, ncb)
+        tiles = {(int(h), int(e), int(r0), int(nb)) for h, e, r0, _, nb in plain if h}
+        assert len(tiles) == (plain[:, 0] > 0).sum()
+        if nk < 16:
+            assert slices == 1
+        n_sliced_cases += slices > 1
+        # ordinal of every 256-row block, experts in order
+        first_rb = np.concatenate([[0], np.cumsum([(c // 256) + (c % 256 > 192) for c in counts])])
+        seen = {}
+        scratch_cells = set()
+        for h, e, r0, nb, z, kt0, n, srow in units:
+            if h == 0:
+                continue
+            key = (int(h), int(e), int(r0), int(nb))
+            assert key in tiles
+            seen.setdefault(key, []).append((int(z), int(kt0), int(n)))
+            height = min(int(h), int(offs[e + 1]) - int(r0))
+            if z == 0:
+                assert srow == -1
+            else:
+                assert 0 <= srow and srow + height <= scratch
+                cells = {(int(srow) + i, int(nb)) for i in range(height)}
+                assert not (cells & scratch_cells)      # no two workgroups write the same partial sums
+                scratch_cells |= cells
+        assert set(seen) == tiles
+        n_units = 0
+        for key, parts in seen.items():
+            parts.sort()
+            h, e, r0, nb = key
+            whole = h == 256 and first_rb[e] + (r0 - offs[e]) // 256 < keep_rb
+            want = 1 if whole else slices
+            n_units += 0 if whole else want
+            assert [z for z, _, _ in parts] == list(range(want))
+            assert parts[0][1] == 0 and sum(n for _, _, n in parts) == nk
+            assert all(a[1] + a[2] == b[1] for a, b in zip(parts, parts[1:]))
+            assert all(n >= 8 for _, _, n in parts) or want == 1
+        assert slices == 1 or n_units <= 256            # what is cut fits one round of workgroups
+        assert keep_rb <= first_rb[-1]
+        if slices > 1:
+            assert (slices - 1) * rows <= scratch
+            # partial sums of one slice tile the compact rows without gaps: cells = rows x column blocks
+            assert len(scratch_cells) == (slices - 1) * rows * ncb
+    assert n_sliced_cases > 0 or nk < 16
 
 
 def test_k_extents_without_a_fast_streaming_kernel_go_to_the_tiled_kernel_early():

@@ -193,24 +193,30 @@ def test_expert_ffn_against_oracle(H, I_s, counts):
     assert _rel(yb[:R], ref) < REL_L2
 
 
-@pytest.mark.parametrize("H,I_s,counts,slices", [
-    (512, 4096, [300, 10], 8),          # 3 row blocks x 2 column blocks
-    (512, 4096, [3000, 2500], 4),       # 22 x 2 tiles
-    (1024, 4096, [0, 4200], 2),         # 17 x 4 tiles, the first expert empty
-    (2048, 1024, [2500, 2100], 1),      # 19 x 8 tiles: enough on their own, written without partial sums
-    (512, 4096, [0, 0], 1),
+@pytest.mark.parametrize("H,I_s,counts,E,slices", [
+    # slices = (256-row blocks whose tiles run whole, K slices of every other tile)
+    (512, 4096, [300, 10], 8, (0, 8)),          # 3 row blocks x 2 column blocks: every tile in 8 K slices
+    (512, 4096, [3000, 2500], 8, (0, 5)),       # 23 x 2 tiles, 64 k-tiles in 5 uneven slices
+    (1024, 4096, [0, 4200], 8, (0, 3)),         # 17 x 4 tiles, the first expert empty
+    (2048, 1024, [2500, 2100], 8, (18, 2)),     # 144 tiles run whole, the 8 remainder tiles in 2 slices
+    (512, 4096, [0, 0], 8, (0, 1)),
+    (2048, 2048, [1300, 40, 800, 2600, 513], 5, (20, 4)),   # 160 tiles whole, 5 x 8 remainder tiles in 4 slices
+    (2048, 2048, [1280, 0, 768, 2560, 512], 5, (20, 1)),    # no remainder tiles, 160 of 256 in the last round: nothing is cut
+    (2048, 1024, [2048, 1536, 1024, 2304, 1792], 5, (32, 2)),   # 272 tiles: the 16 of the last two row blocks in 2 slices
+    (2048, 1024, [2100, 1536, 1024, 2304, 2000], 5, (32, 2)),   # 280 tiles: last three row blocks (one ragged) + remainder tiles
 ])
-def test_expert_ffn_on_a_shard_that_received_far_fewer_rows_than_its_capacity(H, I_s, counts, slices):
-    # a shard with two local experts of eight: how far the down projection is cut along K follows
-    # the routing, not the capacity
-    wg, wu, wd = I.make_expert_weights(0, I.MoEShape("f", H, 2, 1, I_s, True))
+def test_expert_ffn_down_projection_cut_along_k_as_the_routing_asks(H, I_s, counts, E, slices):
+    # how far the down projection is cut along K follows the routing, not the capacity: a shard
+    # that received far fewer rows than its capacity, and the remainder tiles of a large launch
+    n = len(counts)
+    wg, wu, wd = I.make_expert_weights(0, I.MoEShape("f", H, n, 1, I_s, True))
     offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
     R = int(offs[-1])
-    cap = 20000
+    cap = 20000 if E > n else R + 9
     xp = I.make_x(1, cap, H)
-    shard = B.make_shard(8, 2, 2, H, I_s, I_s)
+    shard = B.make_shard(E, n, 0, H, I_s, I_s)
     assert B.moe_debug_ffn_plan(cap, shard)[:2] == (False, False)
-    assert B.moe_debug_down_slices(offs, cap, shard) == slices
+    assert B.moe_debug_down_slices(offs, cap, shard)[:2] == slices
     y = _ffn_gpu(xp, offs, shard, wg, wu, wd)
     assert np.all(np.isnan(y[R:])), "rows past R must not be written"
     if R:
