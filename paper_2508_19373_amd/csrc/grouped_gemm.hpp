@@ -344,18 +344,21 @@ __global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
     const SliceChoice sc = choose_slices(cc, n_col_blocks, nk, max_slices);
     const SlicedUnit u = find_sliced_unit(cc, sc, n_col_blocks, blockIdx.x);
     if (u.cls < 0) return;
-    cls = u.cls == 3 ? 0 : u.cls;
-    tc = (u.cls == 3 || u.cls == 0)
+    if (u.cls == 3) {  // a whole tile: the same call as in the unsliced kernel, constants included
+      tc = locate_full_tile(expert_offsets, n_local, n_col_blocks, sc.keep_rb, false, u.idx);
+      gemm_tile<256, BN, 2, 2, 2, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, 0, K / BK, y);
+      return;
+    }
+    cls = u.cls;
+    tc = (u.cls == 0)
              ? locate_full_tile(expert_offsets, n_local, n_col_blocks, sc.keep_rb, u.cls == 0, u.idx)
              : locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx);
     out = y;
-    if (u.cls != 3) {
-      kt0 = u.z * nk / sc.slices;
-      nk = (u.z + 1) * nk / sc.slices - kt0;
-      if (u.z > 0) {
-        const SlicedRows sr = sliced_rows(expert_offsets, n_local, tc.expert, sc.keep_rb);
-        out = C + ((ptrdiff_t)(u.z - 1) * sr.total + sr.base - sr.first) * n_out;
-      }
+    kt0 = u.z * nk / sc.slices;
+    nk = (u.z + 1) * nk / sc.slices - kt0;
+    if (u.z > 0) {
+      const SlicedRows sr = sliced_rows(expert_offsets, n_local, tc.expert, sc.keep_rb);
+      out = C + ((ptrdiff_t)(u.z - 1) * sr.total + sr.base - sr.first) * n_out;
     }
   } else {
     const Unit u = find_unit(cc, blockIdx.x);

@@ -241,12 +241,14 @@ inline int max_grid(int cap_rows, int n_local, int n_col_blocks) {
   return kNumXcd * ((full + kNumXcd - 1) / kNumXcd + 2 * ((small + kNumXcd - 1) / kNumXcd));
 }
 
-// Grid of the sliced kernel: the whole tiles, and three lists that have at most 256 workgroups
-// each when they are cut along K.
+// Grid of the sliced kernel: the whole tiles, then three lists that either are cut along K (then
+// they have at most 256 workgroups together, 35 per XCD with the rounding of each list) or are the
+// plain 128- and 64-row lists.
 inline int sliced_grid(int cap_rows, int n_local, int n_col_blocks) {
-  int full = (cap_rows / 256 + n_local) * n_col_blocks, small = n_local * n_col_blocks;
-  if (small < 256) small = 256;
-  return kNumXcd * ((full + kNumXcd - 1) / kNumXcd + 256 / kNumXcd + 2 * ((small + kNumXcd - 1) / kNumXcd));
+  const int full = (cap_rows / 256 + n_local) * n_col_blocks, small = n_local * n_col_blocks;
+  int rest = 2 * ((small + kNumXcd - 1) / kNumXcd);
+  if (rest < 256 / kNumXcd + 3) rest = 256 / kNumXcd + 3;
+  return kNumXcd * ((full + kNumXcd - 1) / kNumXcd + rest);
 }
 
 // Tiles a launch is expected to have: every local expert with its expected rows plus a two-sigma
