@@ -12,9 +12,11 @@ namespace gg {
 
 constexpr int kNumXcd = 8;
 
-// Row blocks of one expert: as many 256-row blocks as fit, then the remainder r is covered by
-// the cheapest of {64}, {128}, {128 + 64}, {256} rows, so the padding per expert is below 64
-// rows (padded rows are pure loss: only algorithmic FLOPs count).
+// Row blocks of one expert: as many 256-row blocks as fit; a remainder of up to 64 rows is one
+// 64-row block, of up to 128 rows one 128-row block, and a larger one is padded to a 256-row block.
+// A remainder tile re-streams the expert's weights from HBM, which costs about as much chip time as
+// the MFMA work of one more 256-row block that shares them in L2 with its siblings: two remainder
+// tiles (128 + 64 rows) would cost twice that, so there is never more than one.
 struct RowBlocks {
   int n256, n128, n64;
   __host__ __device__ inline int total() const { return n256 + n128 + n64; }
@@ -22,9 +24,9 @@ struct RowBlocks {
 __host__ __device__ inline RowBlocks row_blocks(int rows) {
   RowBlocks rb;
   const int r = rows & 255;
-  rb.n256 = (rows >> 8) + (r > 192 ? 1 : 0);
-  rb.n128 = (r > 64 && r <= 192) ? 1 : 0;
-  rb.n64 = ((r > 0 && r <= 64) || (r > 128 && r <= 192)) ? 1 : 0;
+  rb.n256 = (rows >> 8) + (r > 128 ? 1 : 0);
+  rb.n128 = (r > 64 && r <= 128) ? 1 : 0;
+  rb.n64 = (r > 0 && r <= 64) ? 1 : 0;
   return rb;
 }
 
@@ -63,7 +65,7 @@ __host__ __device__ inline TileCoord locate_tile(const int32_t* __restrict__ exp
       t.expert = e;
       t.nb = idx / mbs;
       t.row_end = hi;
-      t.row0 = lo + (cls == 0 ? (idx % mbs) * 256 : (cls == 1 ? rb.n256 * 256 : rb.n256 * 256 + rb.n128 * 128));
+      t.row0 = lo + (cls == 0 ? (idx % mbs) * 256 : rb.n256 * 256);
       return t;
     }
     idx -= tiles;
@@ -111,7 +113,7 @@ __host__ __device__ inline Unit find_unit(const ClassCounts& c, int bid) {
 // One workgroup per tile leaves compute units idle for a whole walk over K whenever the tiles do
 // not fill a round of 256: a launch with few tiles (a single shared expert, the cold shard of a
 // skewed expert-parallel split), the last round of the 256-row tiles (544 tiles are 2.1 rounds and
-// take 3), and the remainder phase, where the last, at most 192, rows of every expert are 128- and
+// take 3), and the remainder phase, where the last, at most 128, rows of every expert are 128- or
 // 64-row tiles that re-stream the expert's weights latency-bound.  The tiles of that last round are
 // therefore cut along K into slices that run as separate workgroups: the remainder tiles and the
 // 256-row tiles of the last row blocks (in expert order), as many whole row blocks as the last
