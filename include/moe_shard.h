@@ -152,7 +152,10 @@ int moe_combine(const void* y_perm, const int32_t* slot_row, const float* topk_w
 /* Bytes of scratch moe_permute needs for (T, k, shard); 0 on invalid arguments. */
 size_t moe_workspace_bytes(int32_t T, int32_t k, const moe_shard_t* shard);
 
-/* Bytes of scratch moe_expert_ffn needs for (cap_rows, shard); 0 if none (or invalid arguments). */
+/* Bytes of scratch moe_expert_ffn needs for (cap_rows, shard); 0 if none (or invalid arguments).
+ * It holds the fp32 partial sums of whatever the down projection cuts along K for a routing: a
+ * few slices of cap_rows x H floats in the decoding regime, at most 65536 / ceil(H / 256) rows of
+ * H floats in the prefill regime (whatever the capacity). */
 size_t moe_ffn_workspace_bytes(int32_t cap_rows, const moe_shard_t* shard);
 
 /* Static, NUL-terminated description of a status code. */

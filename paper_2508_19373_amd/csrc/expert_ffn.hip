@@ -64,7 +64,7 @@ hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, i
                      cap_rows, wd, static_cast<const uint16_t*>(nullptr), H, I_s, ws, ncb, yp, sp.max_slices);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
-  hipLaunchKernelGGL(gg::sum_sliced_kernel, dim3(1024), dim3(256), 0, stream, ws, expert_offsets, n_local, ncb,
+  hipLaunchKernelGGL(gg::sum_sliced_kernel, dim3(192, (H + 1023) / 1024), dim3(256), 0, stream, ws, expert_offsets, n_local, ncb,
                      I_s / gg::BK, sp.max_slices, H, yp);
   return hipGetLastError();
 }

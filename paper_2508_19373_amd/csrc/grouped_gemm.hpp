@@ -375,7 +375,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
 }
 
 // y[r, :] += partial sums of slices 1, 2, ... in that order, for the rows the sliced kernel cut
-// along K (it repeats that kernel's decision).  One workgroup per row.
+// along K (it repeats that kernel's decision).  A workgroup adds 1024 columns of one row at a time:
+// grid.x walks the rows, grid.y the column chunks.
 __global__ __launch_bounds__(256) void sum_sliced_kernel(const float* __restrict__ partial,
                                                         const int32_t* __restrict__ expert_offsets, int n_local,
                                                         int n_col_blocks, int nk, int max_slices, int n_out,
@@ -401,7 +402,7 @@ __global__ __launch_bounds__(256) void sum_sliced_kernel(const float* __restrict
     }
     float4* yr = reinterpret_cast<float4*>(y + (size_t)row * n_out);
     const float4* pr = p + (size_t)i * n_out / 4;
-    for (int c = threadIdx.x; c < n_out / 4; c += blockDim.x) {
+    for (int c = blockIdx.y * blockDim.x + threadIdx.x; c < n_out / 4; c += gridDim.y * blockDim.x) {
       float4 acc = yr[c];
       for (int z = 1; z < sc.slices; ++z) {
         const float4 v = pr[(z - 1) * stride + c];

@@ -13,20 +13,23 @@ namespace gg {
 constexpr int kNumXcd = 8;
 
 // Row blocks of one expert: as many 256-row blocks as fit; a remainder of up to 64 rows is one
-// 64-row block, of up to 128 rows one 128-row block, and a larger one is padded to a 256-row block.
-// A remainder tile re-streams the expert's weights from HBM, which costs about as much chip time as
-// the MFMA work of one more 256-row block that shares them in L2 with its siblings: two remainder
-// tiles (128 + 64 rows) would cost twice that, so there is never more than one.
+// 64-row block, of up to 128 rows one 128-row block.  A larger remainder of an expert that has a
+// 256-row block is padded to one more: a remainder tile re-streams the expert's weights from HBM,
+// which costs about as much chip time as the MFMA work of a 256-row block that shares them in L2
+// with its siblings, and 128 + 64 rows would stream them twice.  An expert with fewer than 256 rows
+// has no sibling to share with and its launch is short of tiles anyway: it keeps 128 + 64 up to 192
+// rows (two latency-bound streams on two compute units finish sooner than one).
 struct RowBlocks {
   int n256, n128, n64;
   __host__ __device__ inline int total() const { return n256 + n128 + n64; }
 };
 __host__ __device__ inline RowBlocks row_blocks(int rows) {
   RowBlocks rb;
-  const int r = rows & 255;
-  rb.n256 = (rows >> 8) + (r > 128 ? 1 : 0);
-  rb.n128 = (r > 64 && r <= 128) ? 1 : 0;
-  rb.n64 = (r > 0 && r <= 64) ? 1 : 0;
+  const int q = rows >> 8, r = rows & 255;
+  const int pad = q > 0 ? 128 : 192;  // remainders above this become a 256-row block
+  rb.n256 = q + (r > pad ? 1 : 0);
+  rb.n128 = (r > 64 && r <= pad) ? 1 : 0;
+  rb.n64 = ((r > 0 && r <= 64) || (r > 128 && r <= pad)) ? 1 : 0;
   return rb;
 }
 
@@ -65,7 +68,7 @@ __host__ __device__ inline TileCoord locate_tile(const int32_t* __restrict__ exp
       t.expert = e;
       t.nb = idx / mbs;
       t.row_end = hi;
-      t.row0 = lo + (cls == 0 ? (idx % mbs) * 256 : rb.n256 * 256);
+      t.row0 = lo + (cls == 0 ? (idx % mbs) * 256 : (cls == 1 ? rb.n256 * 256 : rb.n256 * 256 + rb.n128 * 128));
       return t;
     }
     idx -= tiles;
@@ -113,8 +116,8 @@ __host__ __device__ inline Unit find_unit(const ClassCounts& c, int bid) {
 // One workgroup per tile leaves compute units idle for a whole walk over K whenever the tiles do
 // not fill a round of 256: a launch with few tiles (a single shared expert, the cold shard of a
 // skewed expert-parallel split), the last round of the 256-row tiles (544 tiles are 2.1 rounds and
-// take 3), and the remainder phase, where the last, at most 128, rows of every expert are 128- or
-// 64-row tiles that re-stream the expert's weights latency-bound.  The tiles of that last round are
+// take 3), and the remainder phase, where the last rows of every expert are 128- or 64-row tiles
+// that re-stream the expert's weights latency-bound.  The tiles of that last round are
 // therefore cut along K into slices that run as separate workgroups: the remainder tiles and the
 // 256-row tiles of the last row blocks (in expert order), as many whole row blocks as the last
 // round holds.  Slice 0 writes y, slice z >= 1 writes fp32 partial sums that a second kernel adds
@@ -152,7 +155,7 @@ __host__ __device__ inline SliceChoice choose_slices(const ClassCounts& c, int n
 }
 inline int max_k_slices(int K) {
   const int s = K / 64 / 8;
-  return s > 8 ? 8 : (s < 1 ? 1 : s);
+  return s > 16 ? 16 : (s < 1 ? 1 : s);
 }
 // Workgroup -> (tile, slice).  Order: the whole 256-row tiles as in find_unit; then the sliced
 // 256-row tiles, the 128-row and the 64-row tiles, each list repeated once per slice, all tiles of

@@ -24,7 +24,7 @@ def test_routed_experts_switch_regime_near_twenty_rows_per_expert():
     assert B.moe_debug_ffn_plan(32, s) == (True, True, 1, 2)
     assert B.moe_debug_ffn_plan(128, s)[2] == 2
     # the headline prefill shape: tiled kernels; K slices for the remainder tiles only (see below)
-    assert B.moe_debug_ffn_plan(8192, s) == (False, False, 2, 8)
+    assert B.moe_debug_ffn_plan(8192, s) == (False, False, 2, 16)
     assert B.moe_ffn_workspace_bytes(8192, s) == 4096 * 4096 * 4
 
 
@@ -34,11 +34,11 @@ def test_single_shared_expert_never_runs_its_down_projection_on_a_handful_of_til
     for rows in (64, 128, 256, 512, 1024):
         w1, w2, mt, slices = B.moe_debug_ffn_plan(rows, s)
         assert not w1 and not w2 and slices >= 2, rows
-    assert B.moe_debug_ffn_plan(256, s) == (False, False, 2, 8)
-    assert B.moe_debug_down_slices([0, 256], 256, s)[:2] == (0, 8)        # 14 tiles, each in 8 slices
+    assert B.moe_debug_ffn_plan(256, s) == (False, False, 2, 16)
+    assert B.moe_debug_down_slices([0, 256], 256, s)[:2] == (0, 16)       # 14 tiles, each in 16 slices of 20 k-tiles
     assert B.moe_debug_down_slices([0, 1024], 1024, s)[:2] == (0, 4)      # 56 tiles
     assert B.moe_debug_down_slices([0, 4096], 4096, s)[:2] == (16, 1)     # 224 tiles: enough on their own
-    assert B.moe_ffn_workspace_bytes(256, s) == 7 * 256 * 3584 * 4
+    assert B.moe_ffn_workspace_bytes(256, s) == 15 * 256 * 3584 * 4
     assert B.moe_ffn_workspace_bytes(4096, s) == (65536 // 14) * 3584 * 4
 
 
@@ -68,21 +68,21 @@ def test_down_projection_slices_follow_the_routing():
     assert used(300, 100) == (0, 5)      # 3 row blocks (256 + 64, 128): 48 tiles
     assert used(700, 0) == (0, 5)        # 512 + 188 padded to 256: 48 tiles
     assert used(700, 700) == (0, 2)      # 96 tiles
-    assert used(1100, 1000) == (8, 8)    # 8 whole row blocks (128 tiles), the 128-row remainder in 8 slices
+    assert used(1100, 1000) == (8, 16)   # 8 whole row blocks (128 tiles), the 128-row remainder in 16 slices
     assert used(1024, 512) == (0, 2) and used(10240, 5120) == (60, 1)    # no remainder tiles; 960 tiles = 3.75 rounds
-    # the hot shard: 78 + 50 row blocks = 2048 tiles = 8 rounds exactly; the remainder tiles in 8 slices
-    assert used(20000, 12768) == (128, 8)
+    # the hot shard: 78 + 50 row blocks = 2048 tiles = 8 rounds exactly; the remainder tiles in 16 slices
+    assert used(20000, 12768) == (128, 16)
     # 35 row blocks (two of them padded) = 560 tiles = 2.2 rounds: the 48 tiles of the last three in 5 slices
     assert used(5000, 3770) == (32, 5)
     assert used(5120, 3584) == (32, 8)   # 34 row blocks, no remainders: the last two in 8 slices
-    # the scratch is sized for any routing: 65536 / 16 rows, or 7 slices of the capacity
+    # the scratch is sized for any routing: 65536 / 16 rows, or 15 slices of the capacity
     assert B.moe_ffn_workspace_bytes(cap, ep4) == 4096 * 4096 * 4
     # the unsharded layer: 32 row blocks = 512 tiles = 2 rounds; the 3 x 16 remainder tiles in 5 slices
     full = _shard(8, 8, **MIXTRAL)
     counts = (1030, 1000, 1100, 1024, 960, 1090, 1020, 968)
     info = B.moe_debug_down_slices(_offsets(counts), 8192, full)
     assert info[:2] == (32, 5)
-    assert info[2] == sum(c % 256 for c in counts if c % 256 <= 128) and info[3] == 4096
+    assert info[2] == sum(c % 256 for c in counts if c % 256 <= (128 if c >= 256 else 192)) and info[3] == 4096
     with pytest.raises(B.MoeError):
         B.moe_debug_down_slices([0, 5, 3], cap, ep4)
     with pytest.raises(B.MoeError):
@@ -115,7 +115,7 @@ def test_sliced_work_list_covers_every_tile_and_slice_once(E_loc, hidden, inter,
             assert slices == 1
         n_sliced_cases += slices > 1
         # ordinal of every 256-row block, experts in order
-        first_rb = np.concatenate([[0], np.cumsum([(c // 256) + (c % 256 > 128) for c in counts])])
+        first_rb = np.concatenate([[0], np.cumsum([(c // 256) + (c % 256 > (128 if c >= 256 else 192)) for c in counts])])
         seen = {}
         scratch_cells = set()
         for h, e, r0, nb, z, kt0, n, srow in units:

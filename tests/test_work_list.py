@@ -54,16 +54,19 @@ def test_empty_routing_and_single_row():
     assert n == 3 and sorted(int(r[0]) for r in units if r[0]) == [64, 64, 64]
 
 
-def test_one_remainder_tile_at_most_and_padding_below_128_rows():
+def test_remainder_tiles_and_padding():
     # a remainder of up to 64 / up to 128 rows is a 64- / 128-row tile; a larger one is padded to a
-    # 256-row tile (a second remainder tile would stream the expert's weights a second time)
+    # 256-row tile when the expert has a 256-row block to share the weights with (a second
+    # remainder tile would stream them a second time), and is 128 + 64 rows up to 192 otherwise
     for rows in range(1, 1200):
         units, _ = _check_cover(np.array([rows]), rows, 1)
         h = units[:, 0][units[:, 0] > 0]
         r = rows % 256
-        assert (h < 256).sum() == (1 if 0 < r <= 128 else 0)
-        assert h.sum() - rows < (64 if r <= 128 else 128)
-        assert (h == 64).sum() == (0 < r <= 64) and (h == 128).sum() == (64 < r <= 128)
+        pad = 128 if rows >= 256 else 192
+        assert (h == 64).sum() == (0 < r <= 64 or 128 < r <= pad)
+        assert (h == 128).sum() == (64 < r <= pad)
+        assert (h == 256).sum() == rows // 256 + (r > pad)
+        assert h.sum() - rows < (64 if r <= pad else 128)
 
 
 def test_full_tiles_first_and_balanced_over_xcds():
