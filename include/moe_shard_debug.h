@@ -62,6 +62,23 @@ int32_t moe_debug_ffn_plan(int32_t cap_rows, const moe_shard_t* shard, int32_t* 
 int32_t moe_debug_down_slices(const int32_t* expert_offsets, int32_t cap_rows, const moe_shard_t* shard,
                               int32_t* slices, int32_t* units, int32_t max_units);
 
+#define MOE_DEBUG_DEVICE_INTS 9
+
+/*
+ * The same work lists as the two calls above, evaluated on the DEVICE by the wave-parallel code the
+ * GEMM kernels use (one wavefront per workgroup id), for tests that compare it with the host code.
+ * expert_offsets [n_local+1] int32 DEVICE; n_col_blocks, nk (k-tiles of 64): as the kernel is launched
+ * max_slices     0: the plain list of moe_debug_gemm_units; >= 1: the sliced list of
+ *                moe_debug_down_slices with that maximum
+ * units          [max_units][MOE_DEBUG_DEVICE_INTS] int32 DEVICE, written asynchronously on `stream`:
+ *                {tile height (0 = no work), local expert, row0, row_end, column block, slice,
+ *                 first k-tile, k-tiles, scratch row of row0 (-1: writes y_perm)}
+ * Returns the grid size, or a negative MOE_ERR_* code.
+ */
+int32_t moe_debug_device_units(const int32_t* expert_offsets, int32_t n_local, int32_t cap_rows,
+                               int32_t n_col_blocks, int32_t nk, int32_t max_slices, int32_t* units,
+                               int32_t max_units, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

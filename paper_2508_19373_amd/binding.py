@@ -27,11 +27,12 @@ MOE_MAX_TOPK = 16
 
 EXPORTS = ("moe_route_topk", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_workspace_bytes",
            "moe_ffn_workspace_bytes", "moe_status_string")
-DEBUG_EXPORTS = ("moe_debug_gemm_units", "moe_debug_ffn_plan", "moe_debug_down_slices")
+DEBUG_EXPORTS = ("moe_debug_gemm_units", "moe_debug_ffn_plan", "moe_debug_down_slices", "moe_debug_device_units")
 INT4_EXPORTS = ("moe_int4_dequantize", "moe_int4_quantize")
 INT4_GROUP = 64
 DEBUG_UNIT_INTS = 5
 DEBUG_SLICE_INTS = 8
+DEBUG_DEVICE_INTS = 9
 
 
 class MoeShard(ctypes.Structure):
@@ -77,6 +78,8 @@ def lib() -> ctypes.CDLL:
         L.moe_debug_ffn_plan.restype = i32
         L.moe_debug_down_slices.argtypes = [vp, i32, shp, vp, vp, i32]
         L.moe_debug_down_slices.restype = i32
+        L.moe_debug_device_units.argtypes = [vp, i32, i32, i32, i32, i32, vp, i32, vp]
+        L.moe_debug_device_units.restype = i32
         L.moe_debug_gemm_units.argtypes = [vp, i32, i32, i32, vp, i32]
         L.moe_debug_gemm_units.restype = i32
         _lib = L
@@ -195,6 +198,21 @@ def moe_debug_down_slices(expert_offsets, cap_rows, shard: MoeShard, with_units=
     if n < 0:
         raise MoeError("moe_debug_down_slices", n)
     return tuple(info), out[:n]
+
+
+def moe_debug_device_units(expert_offsets, cap_rows, n_col_blocks, nk, max_slices, stream=None):
+    """The GEMM kernels' own (wave-parallel) evaluation of the work list, run on the device:
+    int32 tensor [grid, DEBUG_DEVICE_INTS] (see include/moe_shard_debug.h).  `expert_offsets` is a
+    device int32 tensor."""
+    import torch
+    n_local = expert_offsets.numel() - 1
+    max_units = 8 * ((cap_rows // 256 + n_local) * n_col_blocks // 8 + 1 + 2 * (n_local * n_col_blocks // 8 + 1) + 64)
+    out = torch.full((max_units, DEBUG_DEVICE_INTS), -7, dtype=torch.int32, device=expert_offsets.device)
+    n = lib().moe_debug_device_units(_ptr(expert_offsets), n_local, cap_rows, n_col_blocks, nk, max_slices,
+                                     _ptr(out), max_units, _stream(stream))
+    if n < 0:
+        raise MoeError("moe_debug_device_units", n)
+    return out[:n]
 
 
 def moe_debug_ffn_plan(cap_rows, shard: MoeShard):

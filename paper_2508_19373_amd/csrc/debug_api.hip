@@ -3,7 +3,7 @@
 // routing is covered exactly once.
 #include "moe_shard_debug.h"
 #include "moe_internal.hpp"
-#include "unit_list.hpp"
+#include "unit_list_wave.hpp"
 
 extern "C" int32_t moe_debug_gemm_units(const int32_t* expert_offsets, int32_t n_local, int32_t cap_rows,
                                         int32_t n_col_blocks, int32_t* units,
@@ -85,4 +85,56 @@ extern "C" int32_t moe_debug_down_slices(const int32_t* expert_offsets, int32_t 
     rec[7] = u.z == 0 ? -1 : (u.z - 1) * sr.total + sr.base + tc.row0 - sr.first;
   }
   return grid;
+}
+
+namespace {
+// One wavefront per workgroup id of the GEMM grid: the record the GEMM kernels would act on.
+__global__ __launch_bounds__(64) void device_units_kernel(const int32_t* __restrict__ expert_offsets, int n_local,
+                                                         int n_col_blocks, int nk, int max_slices,
+                                                         int32_t* __restrict__ units) {
+  using namespace moe::gg;
+  int32_t rec[MOE_DEBUG_DEVICE_INTS] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+  if (max_slices == 0) {
+    int cls = 0;
+    TileCoord tc;
+    if (wave_find_tile(expert_offsets, n_local, n_col_blocks, blockIdx.x, cls, tc)) {
+      rec[0] = cls == 0 ? 256 : (cls == 1 ? 128 : 64);
+      rec[1] = tc.expert;
+      rec[2] = tc.row0;
+      rec[3] = tc.row_end;
+      rec[4] = tc.nb;
+      rec[7] = nk;
+      rec[8] = -1;
+    }
+  } else {
+    const WaveSlicedUnit u = wave_find_sliced_unit(expert_offsets, n_local, n_col_blocks, nk, max_slices, blockIdx.x);
+    if (u.valid) {
+      rec[0] = (u.cls == 3 || u.cls == 0) ? 256 : (u.cls == 1 ? 128 : 64);
+      rec[1] = u.tc.expert;
+      rec[2] = u.tc.row0;
+      rec[3] = u.tc.row_end;
+      rec[4] = u.tc.nb;
+      rec[5] = u.z;
+      rec[6] = u.kt0;
+      rec[7] = u.nk;
+      rec[8] = u.z == 0 ? -1 : (int32_t)(u.scratch_shift + u.tc.row0);
+    }
+  }
+  if (threadIdx.x == 0)
+    for (int i = 0; i < MOE_DEBUG_DEVICE_INTS; ++i) units[(size_t)blockIdx.x * MOE_DEBUG_DEVICE_INTS + i] = rec[i];
+}
+}  // namespace
+
+extern "C" int32_t moe_debug_device_units(const int32_t* expert_offsets, int32_t n_local, int32_t cap_rows,
+                                          int32_t n_col_blocks, int32_t nk, int32_t max_slices, int32_t* units,
+                                          int32_t max_units, void* stream) {
+  using namespace moe::gg;
+  if (expert_offsets == nullptr || units == nullptr || n_local < 1 || n_local > MOE_MAX_EXPERTS || cap_rows < 0 ||
+      n_col_blocks < 1 || nk < 1 || max_slices < 0 || max_slices > 16)
+    return MOE_ERR_INVALID_ARG;
+  const int grid = max_slices > 0 ? sliced_grid(cap_rows, n_local, n_col_blocks) : max_grid(cap_rows, n_local, n_col_blocks);
+  if (grid > max_units) return MOE_ERR_WORKSPACE;
+  hipLaunchKernelGGL(device_units_kernel, dim3(grid), dim3(64), 0, static_cast<hipStream_t>(stream), expert_offsets,
+                     n_local, n_col_blocks, nk, max_slices, units);
+  return hipGetLastError() == hipSuccess ? grid : MOE_ERR_HIP;
 }

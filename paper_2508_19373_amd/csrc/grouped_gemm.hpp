@@ -28,7 +28,7 @@
 #include <type_traits>
 
 #include "moe_internal.hpp"
-#include "unit_list.hpp"
+#include "unit_list_wave.hpp"
 
 namespace moe {
 namespace gg {
@@ -336,35 +336,23 @@ __global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
     const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1, int n_out, int K, OutT* __restrict__ C,
     int n_col_blocks, OutT* __restrict__ y, int max_slices) {
   __shared__ __attribute__((aligned(1024))) uint16_t smem[kLdsBytes / 2];
-  const ClassCounts cc = count_tiles(expert_offsets, n_local, n_col_blocks);
   int nk = K / BK, kt0 = 0, cls;
   OutT* out = C;
   TileCoord tc;
   if constexpr (SLICED) {
-    const SliceChoice sc = choose_slices(cc, n_col_blocks, nk, max_slices);
-    const SlicedUnit u = find_sliced_unit(cc, sc, n_col_blocks, blockIdx.x);
-    if (u.cls < 0) return;
+    const WaveSlicedUnit u = wave_find_sliced_unit(expert_offsets, n_local, n_col_blocks, nk, max_slices, blockIdx.x);
+    if (!u.valid) return;
     if (u.cls == 3) {  // a whole tile: the same call as in the unsliced kernel, constants included
-      tc = locate_full_tile(expert_offsets, n_local, n_col_blocks, sc.keep_rb, false, u.idx);
-      gemm_tile<256, BN, 2, 2, 2, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, 0, K / BK, y);
+      gemm_tile<256, BN, 2, 2, 2, 3, GATEUP, OutT>(smem, u.tc, A, cap_rows, B0, B1, n_out, K, 0, K / BK, y);
       return;
     }
     cls = u.cls;
-    tc = (u.cls == 0)
-             ? locate_full_tile(expert_offsets, n_local, n_col_blocks, sc.keep_rb, u.cls == 0, u.idx)
-             : locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx);
-    out = y;
-    kt0 = u.z * nk / sc.slices;
-    nk = (u.z + 1) * nk / sc.slices - kt0;
-    if (u.z > 0) {
-      const SlicedRows sr = sliced_rows(expert_offsets, n_local, tc.expert, sc.keep_rb);
-      out = C + ((ptrdiff_t)(u.z - 1) * sr.total + sr.base - sr.first) * n_out;
-    }
+    tc = u.tc;
+    kt0 = u.kt0;
+    nk = u.nk;
+    out = u.z == 0 ? y : C + u.scratch_shift * n_out;
   } else {
-    const Unit u = find_unit(cc, blockIdx.x);
-    if (u.cls < 0) return;
-    cls = u.cls;
-    tc = locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx);
+    if (!wave_find_tile(expert_offsets, n_local, n_col_blocks, blockIdx.x, cls, tc)) return;
   }
   if (cls == 0)
     gemm_tile<256, BN, 2, 2, 2, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out);
@@ -381,25 +369,16 @@ __global__ __launch_bounds__(256) void sum_sliced_kernel(const float* __restrict
                                                         const int32_t* __restrict__ expert_offsets, int n_local,
                                                         int n_col_blocks, int nk, int max_slices, int n_out,
                                                         float* __restrict__ y) {
-  const ClassCounts cc = count_tiles(expert_offsets, n_local, n_col_blocks);
-  const SliceChoice sc = choose_slices(cc, n_col_blocks, nk, max_slices);
+  const WaveRouting w = wave_routing(expert_offsets, n_local, n_col_blocks);
+  const SliceChoice sc = choose_slices(w.cc, n_col_blocks, nk, max_slices);
   if (sc.slices == 1) return;
-  const int total = sliced_rows(expert_offsets, n_local, 0, sc.keep_rb).total;
+  const WaveSliced sr = wave_sliced_rows(w, sc.keep_rb);
+  const int total = sr.total;
   const size_t stride = (size_t)total * n_out / 4;
   const float4* p = reinterpret_cast<const float4*>(partial);
   for (int i = blockIdx.x; i < total; i += gridDim.x) {
-    int row = 0, base = 0, before = 0;
-    for (int e = 0; e < n_local; ++e) {
-      const int lo = expert_offsets[e], hi = expert_offsets[e + 1];
-      const int n256 = row_blocks(hi - lo).n256;
-      const int first = min(hi, lo + min(max(sc.keep_rb - before, 0), n256) * 256);
-      if (i < base + hi - first) {
-        row = first + i - base;
-        break;
-      }
-      base += hi - first;
-      before += n256;
-    }
+    const WaveHit h = wave_find(sr.pre_cnt, sr.cnt, w.chunks, i);
+    const int row = wave_pick(w.lo, h) + min(wave_pick(w.rows, h), wave_pick(sr.kept, h) * 256) + i - wave_pick(sr.pre_cnt, h);
     float4* yr = reinterpret_cast<float4*>(y + (size_t)row * n_out);
     const float4* pr = p + (size_t)i * n_out / 4;
     for (int c = blockIdx.y * blockDim.x + threadIdx.x; c < n_out / 4; c += gridDim.y * blockDim.x) {
