@@ -97,7 +97,7 @@ __global__ __launch_bounds__(64) void device_units_kernel(const int32_t* __restr
   if (max_slices == 0) {
     int cls = 0;
     TileCoord tc;
-    if (wave_find_tile(expert_offsets, n_local, n_col_blocks, blockIdx.x, cls, tc)) {
+    if (find_tile(expert_offsets, n_local, n_col_blocks, blockIdx.x, cls, tc)) {
       rec[0] = cls == 0 ? 256 : (cls == 1 ? 128 : 64);
       rec[1] = tc.expert;
       rec[2] = tc.row0;
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(64) void device_units_kernel(const int32_t* __restr
       rec[8] = -1;
     }
   } else {
-    const WaveSlicedUnit u = wave_find_sliced_unit(expert_offsets, n_local, n_col_blocks, nk, max_slices, blockIdx.x);
+    const WaveSlicedUnit u = find_sliced_unit_of(expert_offsets, n_local, n_col_blocks, nk, max_slices, blockIdx.x);
     if (u.valid) {
       rec[0] = (u.cls == 3 || u.cls == 0) ? 256 : (u.cls == 1 ? 128 : 64);
       rec[1] = u.tc.expert;

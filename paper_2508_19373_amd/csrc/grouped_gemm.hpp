@@ -340,7 +340,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
   OutT* out = C;
   TileCoord tc;
   if constexpr (SLICED) {
-    const WaveSlicedUnit u = wave_find_sliced_unit(expert_offsets, n_local, n_col_blocks, nk, max_slices, blockIdx.x);
+    const WaveSlicedUnit u = find_sliced_unit_of(expert_offsets, n_local, n_col_blocks, nk, max_slices, blockIdx.x);
     if (!u.valid) return;
     if (u.cls == 3) {  // a whole tile: the same call as in the unsliced kernel, constants included
       gemm_tile<256, BN, 2, 2, 2, 3, GATEUP, OutT>(smem, u.tc, A, cap_rows, B0, B1, n_out, K, 0, K / BK, y);
@@ -352,7 +352,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
     nk = u.nk;
     out = u.z == 0 ? y : C + u.scratch_shift * n_out;
   } else {
-    if (!wave_find_tile(expert_offsets, n_local, n_col_blocks, blockIdx.x, cls, tc)) return;
+    if (!find_tile(expert_offsets, n_local, n_col_blocks, blockIdx.x, cls, tc)) return;
   }
   if (cls == 0)
     gemm_tile<256, BN, 2, 2, 2, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out);
@@ -369,26 +369,30 @@ __global__ __launch_bounds__(256) void sum_sliced_kernel(const float* __restrict
                                                         const int32_t* __restrict__ expert_offsets, int n_local,
                                                         int n_col_blocks, int nk, int max_slices, int n_out,
                                                         float* __restrict__ y) {
-  const WaveRouting w = wave_routing(expert_offsets, n_local, n_col_blocks);
-  const SliceChoice sc = choose_slices(w.cc, n_col_blocks, nk, max_slices);
-  if (sc.slices == 1) return;
-  const WaveSliced sr = wave_sliced_rows(w, sc.keep_rb);
-  const int total = sr.total;
+  const SumPlan plan = sum_plan(expert_offsets, n_local, n_col_blocks, nk, max_slices);
+  if (plan.slices == 1) return;
+  const int total = plan.total;
   const size_t stride = (size_t)total * n_out / 4;
   const float4* p = reinterpret_cast<const float4*>(partial);
   for (int i = blockIdx.x; i < total; i += gridDim.x) {
-    const WaveHit h = wave_find(sr.pre_cnt, sr.cnt, w.chunks, i);
-    const int row = wave_pick(w.lo, h) + min(wave_pick(w.rows, h), wave_pick(sr.kept, h) * 256) + i - wave_pick(sr.pre_cnt, h);
+    const int row = sum_plan_row(plan, expert_offsets, n_local, i);
     float4* yr = reinterpret_cast<float4*>(y + (size_t)row * n_out);
     const float4* pr = p + (size_t)i * n_out / 4;
     for (int c = blockIdx.y * blockDim.x + threadIdx.x; c < n_out / 4; c += gridDim.y * blockDim.x) {
+      // all loads first (one memory latency instead of one per slice), then the sum in slice order
+      float4 v[kMaxKSlices - 1];
+#pragma unroll
+      for (int z = 1; z < kMaxKSlices; ++z)
+        if (z < plan.slices) v[z - 1] = pr[(z - 1) * stride + c];
       float4 acc = yr[c];
-      for (int z = 1; z < sc.slices; ++z) {
-        const float4 v = pr[(z - 1) * stride + c];
-        acc.x += v.x;
-        acc.y += v.y;
-        acc.z += v.z;
-        acc.w += v.w;
+#pragma unroll
+      for (int z = 1; z < kMaxKSlices; ++z) {
+        if (z < plan.slices) {
+          acc.x += v[z - 1].x;
+          acc.y += v[z - 1].y;
+          acc.z += v[z - 1].z;
+          acc.w += v[z - 1].w;
+        }
       }
       yr[c] = acc;
     }

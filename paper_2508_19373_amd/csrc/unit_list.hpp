@@ -123,14 +123,23 @@ __host__ __device__ inline Unit find_unit(const ClassCounts& c, int bid) {
 // round holds.  Slice 0 writes y, slice z >= 1 writes fp32 partial sums that a second kernel adds
 // to y in slice order.
 //
-// fit_slices: as many slices as keep `n_tiles` tiles within 256 workgroups, at most `max_slices`,
-// at least 8 k-tiles each.
-__host__ __device__ inline int fit_slices(int n_tiles, int nk, int max_slices) {
+// fit_slices: the number of slices s <= min(max_slices, 256 / n_tiles, nk / 8) that minimises an
+// estimate of the run time, in sixteenths of one k-tile step (1.1-1.3 us): the walk, nk / s, and
+// for s > 1 the second kernel, 4 steps for its launch plus rows * n_col_blocks * (s + 1) / 4400 for
+// reading s - 1 partial sums of `rows` rows and updating y at about 4 TB/s.  (Measured: 120
+// remainder tiles of 22 k-tiles and 1500 rows are not worth cutting in two, 16 tiles of 88 k-tiles
+// and 512 rows are worth cutting in 11.)
+__host__ __device__ inline int fit_slices(int n_tiles, int nk, int max_slices, int rows, int n_col_blocks) {
   if (n_tiles <= 0) return 1;
-  int s = 256 / n_tiles;
-  if (s > max_slices) s = max_slices;
-  if (s > nk / 8) s = nk / 8;
-  return s < 1 ? 1 : s;
+  int hi = 256 / n_tiles;
+  if (hi > max_slices) hi = max_slices;
+  if (hi > nk / 8) hi = nk / 8;
+  int best = 1, best_cost = nk * 16;
+  for (int s = 2; s <= hi; ++s) {
+    const int cost = (nk * 16 + s - 1) / s + 64 + rows * n_col_blocks * (s + 1) / 275;
+    if (cost < best_cost) best = s, best_cost = cost;
+  }
+  return best;
 }
 // keep_rb: 256-row blocks (counted over the experts in order) whose tiles run whole; the tiles of
 // all later 256-row blocks and all remainder tiles run in `slices` K slices.
@@ -140,6 +149,7 @@ struct SliceChoice {
 __host__ __device__ inline SliceChoice choose_slices(const ClassCounts& c, int n_col_blocks, int nk,
                                                      int max_slices) {
   const int n_rb = c.n[0] / n_col_blocks, n_small = c.n[1] + c.n[2];
+  const int small_rows = c.n[1] / n_col_blocks * 128 + c.n[2] / n_col_blocks * 64;  // at most
   int tail_rb = 0;
   if (c.n[0] + n_small <= 128) {
     tail_rb = n_rb;  // less than half a round in all
@@ -148,14 +158,18 @@ __host__ __device__ inline SliceChoice choose_slices(const ClassCounts& c, int n
     if (last > 0 && last <= 128) tail_rb = (last + n_col_blocks - 1) / n_col_blocks;
   }
   SliceChoice sc;
-  sc.slices = fit_slices(tail_rb * n_col_blocks + n_small, nk, max_slices);
-  if (sc.slices == 1 && n_small > 0) sc.slices = fit_slices(n_small, nk, max_slices), tail_rb = 0;
+  sc.slices = fit_slices(tail_rb * n_col_blocks + n_small, nk, max_slices, tail_rb * 256 + small_rows, n_col_blocks);
+  if (sc.slices == 1 && n_small > 0 && tail_rb > 0) {
+    sc.slices = fit_slices(n_small, nk, max_slices, small_rows, n_col_blocks);
+    tail_rb = 0;
+  }
   sc.keep_rb = sc.slices > 1 ? n_rb - tail_rb : n_rb;
   return sc;
 }
+constexpr int kMaxKSlices = 16;
 inline int max_k_slices(int K) {
   const int s = K / 64 / 8;
-  return s > 16 ? 16 : (s < 1 ? 1 : s);
+  return s > kMaxKSlices ? kMaxKSlices : (s < 1 ? 1 : s);
 }
 // Workgroup -> (tile, slice).  Order: the whole 256-row tiles as in find_unit; then the sliced
 // 256-row tiles, the 128-row and the 64-row tiles, each list repeated once per slice, all tiles of

@@ -215,5 +215,99 @@ __device__ inline WaveSlicedUnit wave_find_sliced_unit(const int32_t* __restrict
   return r;
 }
 
+// ---- dispatch: a handful of experts are walked faster by the plain loops ---------------------------
+// (the wave version costs a fixed 1-2 us of loads and cross-lane steps per workgroup, which shows on
+// the short launches of expert-parallel shards with one or two experts)
+constexpr int kPlainLoopExperts = 4;
+
+__device__ inline bool find_tile(const int32_t* __restrict__ expert_offsets, int n_local, int n_col_blocks, int bid,
+                                 int& cls, TileCoord& tc) {
+  if (n_local > kPlainLoopExperts) return wave_find_tile(expert_offsets, n_local, n_col_blocks, bid, cls, tc);
+  const ClassCounts cc = count_tiles(expert_offsets, n_local, n_col_blocks);
+  const Unit u = find_unit(cc, bid);
+  if (u.cls < 0) return false;
+  cls = u.cls;
+  tc = locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx);
+  return true;
+}
+
+__device__ inline WaveSlicedUnit find_sliced_unit_of(const int32_t* __restrict__ expert_offsets, int n_local,
+                                                     int n_col_blocks, int nk_all, int max_slices, int bid) {
+  if (n_local > kPlainLoopExperts)
+    return wave_find_sliced_unit(expert_offsets, n_local, n_col_blocks, nk_all, max_slices, bid);
+  WaveSlicedUnit r;
+  r.valid = false;
+  const ClassCounts cc = count_tiles(expert_offsets, n_local, n_col_blocks);
+  const SliceChoice sc = choose_slices(cc, n_col_blocks, nk_all, max_slices);
+  const SlicedUnit u = find_sliced_unit(cc, sc, n_col_blocks, bid);
+  if (u.cls < 0) return r;
+  r.valid = true;
+  r.cls = u.cls;
+  r.z = u.z;
+  r.kt0 = 0;
+  r.nk = nk_all;
+  r.scratch_shift = 0;
+  r.tc = (u.cls == 3 || u.cls == 0)
+             ? locate_full_tile(expert_offsets, n_local, n_col_blocks, sc.keep_rb, u.cls == 0, u.idx)
+             : locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx);
+  if (u.cls != 3) {
+    r.kt0 = u.z * nk_all / sc.slices;
+    r.nk = (u.z + 1) * nk_all / sc.slices - r.kt0;
+    if (u.z > 0) {
+      const SlicedRows sr = sliced_rows(expert_offsets, n_local, r.tc.expert, sc.keep_rb);
+      r.scratch_shift = (long)(u.z - 1) * sr.total + sr.base - sr.first;
+    }
+  }
+  return r;
+}
+
+// The rows with partial sums, for the kernel that adds them: slices (1: nothing to add), their
+// number, and the row behind compact number i.
+struct SumPlan {
+  int slices, total, keep_rb;
+  bool plain;
+  WaveRouting w;
+  WaveSliced s;
+};
+__device__ inline SumPlan sum_plan(const int32_t* __restrict__ expert_offsets, int n_local, int n_col_blocks,
+                                   int nk_all, int max_slices) {
+  SumPlan p;
+  p.plain = n_local <= kPlainLoopExperts;
+  p.total = 0;
+  if (p.plain) {
+    const ClassCounts cc = count_tiles(expert_offsets, n_local, n_col_blocks);
+    const SliceChoice sc = choose_slices(cc, n_col_blocks, nk_all, max_slices);
+    p.slices = sc.slices;
+    p.keep_rb = sc.keep_rb;
+    if (sc.slices > 1) p.total = sliced_rows(expert_offsets, n_local, 0, sc.keep_rb).total;
+  } else {
+    p.w = wave_routing(expert_offsets, n_local, n_col_blocks);
+    const SliceChoice sc = choose_slices(p.w.cc, n_col_blocks, nk_all, max_slices);
+    p.slices = sc.slices;
+    p.keep_rb = sc.keep_rb;
+    if (sc.slices > 1) {
+      p.s = wave_sliced_rows(p.w, sc.keep_rb);
+      p.total = p.s.total;
+    }
+  }
+  return p;
+}
+__device__ inline int sum_plan_row(const SumPlan& p, const int32_t* __restrict__ expert_offsets, int n_local, int i) {
+  if (!p.plain) {
+    const WaveHit h = wave_find(p.s.pre_cnt, p.s.cnt, p.w.chunks, i);
+    return wave_pick(p.w.lo, h) + min(wave_pick(p.w.rows, h), wave_pick(p.s.kept, h) * 256) + i - wave_pick(p.s.pre_cnt, h);
+  }
+  int base = 0, before = 0;
+  for (int e = 0; e < n_local; ++e) {
+    const int lo = expert_offsets[e], hi = expert_offsets[e + 1];
+    const int n256 = row_blocks(hi - lo).n256;
+    const int first = min(hi, lo + min(max(p.keep_rb - before, 0), n256) * 256);
+    if (i < base + hi - first) return first + i - base;
+    base += hi - first;
+    before += n256;
+  }
+  return 0;
+}
+
 }  // namespace gg
 }  // namespace moe

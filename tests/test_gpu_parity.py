@@ -203,7 +203,7 @@ def test_expert_ffn_against_oracle(H, I_s, counts):
     (2048, 2048, [1300, 40, 800, 2600, 513], 5, (20, 4)),   # 160 tiles whole, 5 x 8 remainder tiles in 4 slices
     (2048, 2048, [1280, 0, 768, 2560, 512], 5, (20, 1)),    # no remainder tiles, 160 of 256 in the last round: nothing is cut
     (2048, 1024, [2048, 1536, 1024, 2304, 1792], 5, (32, 2)),   # 272 tiles: the 16 of the last two row blocks in 2 slices
-    (2048, 1024, [2100, 1536, 1024, 2304, 2000], 5, (32, 2)),   # 280 tiles: last three row blocks (one ragged) + remainder tiles
+    (2048, 2048, [2100, 1536, 1024, 2304, 2000], 5, (32, 4)),   # 280 tiles: last three row blocks (one ragged) + remainder tiles
 ])
 def test_expert_ffn_down_projection_cut_along_k_as_the_routing_asks(H, I_s, counts, E, slices):
     # how far the down projection is cut along K follows the routing, not the capacity: a shard

@@ -1,6 +1,6 @@
 """The GEMM kernels evaluate their work list with wave-parallel code (prefix sums and ballots over
-the experts); the plain loops in the same library, which the CPU tests check against the definition,
-are the reference.  Both must agree on every workgroup of every routing: bit-exact integer work."""
+the experts) when a shard has more than a handful of experts; the plain loops in the same library,
+which the CPU tests check against the definition, are the reference.  Both must agree on every workgroup of every routing: bit-exact integer work."""
 import numpy as np
 import pytest
 import torch
@@ -40,6 +40,10 @@ def _routings(rng, n_local, max_rows):
     (256, 1, 128, 16, 40000),     # the most experts the library takes
     (256, 5, 16, 0, 40000),
     (3, 1, 16, 2, 900),
+    (4, 16, 224, 16, 6000),       # the last count the kernels walk with plain loops ...
+    (5, 16, 224, 16, 6000),       # ... and the first they take wave-parallel
+    (4, 28, 64, 0, 6000),
+    (5, 28, 64, 0, 6000),
 ])
 def test_wave_parallel_work_list_equals_the_plain_one(n_local, ncb, nk, max_slices, max_rows):
     rng = np.random.default_rng(n_local * 7919 + ncb)
