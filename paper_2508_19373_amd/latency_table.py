@@ -34,7 +34,7 @@ def legal_shards(shape, max_devices=8):
     return out
 
 
-def measure(shape, tokens, seed=0, steps=30, warmup=15):
+def measure(shape, tokens, seed=0, steps=60, warmup=30):
     import numpy as np
     import torch
     from . import inputs as I
