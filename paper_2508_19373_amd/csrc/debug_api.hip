@@ -22,7 +22,7 @@ extern "C" int32_t moe_debug_gemm_units(const int32_t* expert_offsets, int32_t n
     for (int i = 0; i < MOE_DEBUG_UNIT_INTS; ++i) rec[i] = 0;
     const Unit u = find_unit(cc, b);
     if (u.cls < 0) continue;
-    const TileCoord tc = locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx);
+    const TileCoord tc = locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx, cc.pad_low);
     rec[0] = u.cls == 0 ? 256 : (u.cls == 1 ? 128 : 64);
     rec[1] = tc.expert;
     rec[2] = tc.row0;
@@ -59,7 +59,7 @@ extern "C" int32_t moe_debug_down_slices(const int32_t* expert_offsets, int32_t 
   const SliceChoice sc = choose_slices(cc, ncb, nk, sp.max_slices);
   slices[0] = sc.keep_rb;
   slices[1] = sc.slices;
-  slices[2] = sc.slices > 1 ? sliced_rows(expert_offsets, n_local, 0, sc.keep_rb).total : 0;
+  slices[2] = sc.slices > 1 ? sliced_rows(expert_offsets, n_local, 0, sc.keep_rb, cc.pad_low).total : 0;
   slices[3] = sp.scratch_rows;
   const int grid = sp.max_slices > 1 ? sliced_grid(cap_rows, n_local, ncb) : max_grid(cap_rows, n_local, ncb);
   if (units == nullptr) return grid;
@@ -70,11 +70,11 @@ extern "C" int32_t moe_debug_down_slices(const int32_t* expert_offsets, int32_t 
     const SlicedUnit u = find_sliced_unit(cc, sc, ncb, b);
     if (u.cls < 0) continue;
     const TileCoord tc = (u.cls == 3 || u.cls == 0)
-                             ? locate_full_tile(expert_offsets, n_local, ncb, sc.keep_rb, u.cls == 0, u.idx)
-                             : locate_tile(expert_offsets, n_local, ncb, u.cls, u.idx);
+                             ? locate_full_tile(expert_offsets, n_local, ncb, sc.keep_rb, u.cls == 0, u.idx, cc.pad_low)
+                             : locate_tile(expert_offsets, n_local, ncb, u.cls, u.idx, cc.pad_low);
     const int s = u.cls == 3 ? 1 : sc.slices;
     const int kt0 = u.z * nk / s;
-    const SlicedRows sr = sliced_rows(expert_offsets, n_local, tc.expert, sc.keep_rb);
+    const SlicedRows sr = sliced_rows(expert_offsets, n_local, tc.expert, sc.keep_rb, cc.pad_low);
     rec[0] = (u.cls == 3 || u.cls == 0) ? 256 : (u.cls == 1 ? 128 : 64);
     rec[1] = tc.expert;
     rec[2] = tc.row0;

@@ -13,20 +13,23 @@ namespace gg {
 constexpr int kNumXcd = 8;
 
 // Row blocks of one expert: as many 256-row blocks as fit; a remainder of up to 64 rows is one
-// 64-row block, of up to 128 rows one 128-row block.  A larger remainder of an expert that has a
-// 256-row block is padded to one more: a remainder tile re-streams the expert's weights from HBM,
-// which costs about as much chip time as the MFMA work of a 256-row block that shares them in L2
-// with its siblings, and 128 + 64 rows would stream them twice.  An expert with fewer than 256 rows
-// has no sibling to share with and its launch is short of tiles anyway: it keeps 128 + 64 up to 192
-// rows (two latency-bound streams on two compute units finish sooner than one).
+// 64-row block, of up to 128 rows one 128-row block.  A larger remainder is padded to one more
+// 256-row block if the expert has a 256-row block already: a remainder tile re-streams the expert's
+// weights from HBM, which costs about as much chip time as the MFMA work of a 256-row block that
+// shares them in L2 with its siblings, and 128 + 64 rows would stream them twice.  An expert with
+// 129 to 192 rows has no sibling to share with.  In a launch that fills the chip (`pad_low`, see
+// count_tiles) it is padded to one 256-row block all the same, because that launch is bound by HBM
+// and the second stream is pure loss (Mixtral at 128 rows per expert: 892 -> 673 us per layer); in
+// a launch short of tiles it keeps 128 + 64, whose deeper pipelines stream faster per compute unit
+// (a single expert of 181 rows: GEMM1 72 against 81 us).
 struct RowBlocks {
   int n256, n128, n64;
   __host__ __device__ inline int total() const { return n256 + n128 + n64; }
 };
-__host__ __device__ inline RowBlocks row_blocks(int rows) {
+__host__ __device__ inline RowBlocks row_blocks(int rows, bool pad_low) {
   RowBlocks rb;
   const int q = rows >> 8, r = rows & 255;
-  const int pad = q > 0 ? 128 : 192;  // remainders above this become a 256-row block
+  const int pad = (q > 0 || pad_low) ? 128 : 192;  // remainders above this become a 256-row block
   rb.n256 = q + (r > pad ? 1 : 0);
   rb.n128 = (r > 64 && r <= pad) ? 1 : 0;
   rb.n64 = ((r > 0 && r <= 64) || (r > 128 && r <= pad)) ? 1 : 0;
@@ -38,14 +41,21 @@ struct TileCoord {
 };
 
 // Tiles per height class (0: 256 rows, 1: 128, 2: 64), over all local experts and column blocks.
+// pad_low: the launch has at least 256 tiles before any padding of experts below 256 rows, that is,
+// it fills every compute unit (every function below takes the flag from here).
 struct ClassCounts {
   int n[3];
+  bool pad_low;
 };
+constexpr int kPadLowTiles = 256;
 __host__ __device__ inline ClassCounts count_tiles(const int32_t* __restrict__ expert_offsets, int n_local,
                                                    int n_col_blocks) {
-  ClassCounts c = {{0, 0, 0}};
+  ClassCounts c = {{0, 0, 0}, false};
+  int blocks = 0;
+  for (int e = 0; e < n_local; ++e) blocks += row_blocks(expert_offsets[e + 1] - expert_offsets[e], false).total();
+  c.pad_low = blocks * n_col_blocks >= kPadLowTiles;
   for (int e = 0; e < n_local; ++e) {
-    const RowBlocks rb = row_blocks(expert_offsets[e + 1] - expert_offsets[e]);
+    const RowBlocks rb = row_blocks(expert_offsets[e + 1] - expert_offsets[e], c.pad_low);
     c.n[0] += rb.n256 * n_col_blocks;
     c.n[1] += rb.n128 * n_col_blocks;
     c.n[2] += rb.n64 * n_col_blocks;
@@ -57,11 +67,11 @@ __host__ __device__ inline ClassCounts count_tiles(const int32_t* __restrict__ e
 // inside a column block the row blocks of that class (row block fastest, so neighbours share the
 // weight panel and a run of tiles covers all full row blocks of a few column blocks).
 __host__ __device__ inline TileCoord locate_tile(const int32_t* __restrict__ expert_offsets, int n_local,
-                                                 int n_col_blocks, int cls, int idx) {
+                                                 int n_col_blocks, int cls, int idx, bool pad_low) {
   TileCoord t = {0, 0, 0, 0};
   for (int e = 0; e < n_local; ++e) {
     const int lo = expert_offsets[e], hi = expert_offsets[e + 1];
-    const RowBlocks rb = row_blocks(hi - lo);
+    const RowBlocks rb = row_blocks(hi - lo, pad_low);
     const int mbs = cls == 0 ? rb.n256 : (cls == 1 ? rb.n128 : rb.n64);
     const int tiles = mbs * n_col_blocks;
     if (idx < tiles) {
@@ -203,12 +213,13 @@ __host__ __device__ inline SlicedUnit find_sliced_unit(const ClassCounts& c, con
 // 256-row tile `idx` among the whole ones (tail = false) or among the sliced ones (tail = true):
 // experts in order, column blocks, row blocks fastest, as locate_tile.
 __host__ __device__ inline TileCoord locate_full_tile(const int32_t* __restrict__ expert_offsets, int n_local,
-                                                      int n_col_blocks, int keep_rb, bool tail, int idx) {
+                                                      int n_col_blocks, int keep_rb, bool tail, int idx,
+                                                      bool pad_low) {
   TileCoord t = {0, 0, 0, 0};
   int before = 0;
   for (int e = 0; e < n_local; ++e) {
     const int lo = expert_offsets[e], hi = expert_offsets[e + 1];
-    const int n256 = row_blocks(hi - lo).n256;
+    const int n256 = row_blocks(hi - lo, pad_low).n256;
     const int kept = min(max(keep_rb - before, 0), n256);
     const int mbs = tail ? n256 - kept : kept;
     const int tiles = mbs * n_col_blocks;
@@ -233,12 +244,12 @@ struct SlicedRows {
   int base, first, total;
 };
 __host__ __device__ inline SlicedRows sliced_rows(const int32_t* __restrict__ expert_offsets, int n_local, int e,
-                                                  int keep_rb) {
+                                                  int keep_rb, bool pad_low) {
   SlicedRows r = {0, 0, 0};
   int before = 0;
   for (int i = 0; i < n_local; ++i) {
     const int lo = expert_offsets[i], hi = expert_offsets[i + 1];
-    const int n256 = row_blocks(hi - lo).n256;
+    const int n256 = row_blocks(hi - lo, pad_low).n256;
     const int first = min(hi, lo + min(max(keep_rb - before, 0), n256) * 256);
     if (i == e) {
       r.base = r.total;

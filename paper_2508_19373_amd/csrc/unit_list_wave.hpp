@@ -83,14 +83,20 @@ __device__ inline WaveRouting wave_routing(const int32_t* __restrict__ expert_of
   WaveRouting w;
   const int lane = threadIdx.x & 63;
   w.chunks = (n_local + 63) >> 6;
-  int t128 = 0, t64 = 0;
+  int blocks = 0;  // this lane's row blocks before any padding of experts below 256 rows
 #pragma unroll
   for (int j = 0; j < kLaneChunks; ++j) {
     const int e = lane + 64 * j;
     const bool ok = j < w.chunks && e < n_local;
     w.lo[j] = ok ? expert_offsets[e] : 0;
     w.rows[j] = ok ? expert_offsets[e + 1] - w.lo[j] : 0;
-    const RowBlocks rb = row_blocks(w.rows[j]);
+    blocks += row_blocks(w.rows[j], false).total();
+  }
+  w.cc.pad_low = __builtin_amdgcn_readlane(wave_incl_scan(blocks), 63) * n_col_blocks >= kPadLowTiles;
+  int t128 = 0, t64 = 0;
+#pragma unroll
+  for (int j = 0; j < kLaneChunks; ++j) {
+    const RowBlocks rb = row_blocks(w.rows[j], w.cc.pad_low);
     w.n256[j] = rb.n256;
     w.n128[j] = rb.n128;
     w.n64[j] = rb.n64;
@@ -227,7 +233,7 @@ __device__ inline bool find_tile(const int32_t* __restrict__ expert_offsets, int
   const Unit u = find_unit(cc, bid);
   if (u.cls < 0) return false;
   cls = u.cls;
-  tc = locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx);
+  tc = locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx, cc.pad_low);
   return true;
 }
 
@@ -248,13 +254,13 @@ __device__ inline WaveSlicedUnit find_sliced_unit_of(const int32_t* __restrict__
   r.nk = nk_all;
   r.scratch_shift = 0;
   r.tc = (u.cls == 3 || u.cls == 0)
-             ? locate_full_tile(expert_offsets, n_local, n_col_blocks, sc.keep_rb, u.cls == 0, u.idx)
-             : locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx);
+             ? locate_full_tile(expert_offsets, n_local, n_col_blocks, sc.keep_rb, u.cls == 0, u.idx, cc.pad_low)
+             : locate_tile(expert_offsets, n_local, n_col_blocks, u.cls, u.idx, cc.pad_low);
   if (u.cls != 3) {
     r.kt0 = u.z * nk_all / sc.slices;
     r.nk = (u.z + 1) * nk_all / sc.slices - r.kt0;
     if (u.z > 0) {
-      const SlicedRows sr = sliced_rows(expert_offsets, n_local, r.tc.expert, sc.keep_rb);
+      const SlicedRows sr = sliced_rows(expert_offsets, n_local, r.tc.expert, sc.keep_rb, cc.pad_low);
       r.scratch_shift = (long)(u.z - 1) * sr.total + sr.base - sr.first;
     }
   }
@@ -265,7 +271,7 @@ __device__ inline WaveSlicedUnit find_sliced_unit_of(const int32_t* __restrict__
 // number, and the row behind compact number i.
 struct SumPlan {
   int slices, total, keep_rb;
-  bool plain;
+  bool plain, pad_low;
   WaveRouting w;
   WaveSliced s;
 };
@@ -274,12 +280,14 @@ __device__ inline SumPlan sum_plan(const int32_t* __restrict__ expert_offsets, i
   SumPlan p;
   p.plain = n_local <= kPlainLoopExperts;
   p.total = 0;
+  p.pad_low = false;
   if (p.plain) {
     const ClassCounts cc = count_tiles(expert_offsets, n_local, n_col_blocks);
     const SliceChoice sc = choose_slices(cc, n_col_blocks, nk_all, max_slices);
     p.slices = sc.slices;
     p.keep_rb = sc.keep_rb;
-    if (sc.slices > 1) p.total = sliced_rows(expert_offsets, n_local, 0, sc.keep_rb).total;
+    p.pad_low = cc.pad_low;
+    if (sc.slices > 1) p.total = sliced_rows(expert_offsets, n_local, 0, sc.keep_rb, cc.pad_low).total;
   } else {
     p.w = wave_routing(expert_offsets, n_local, n_col_blocks);
     const SliceChoice sc = choose_slices(p.w.cc, n_col_blocks, nk_all, max_slices);
@@ -300,7 +308,7 @@ __device__ inline int sum_plan_row(const SumPlan& p, const int32_t* __restrict__
   int base = 0, before = 0;
   for (int e = 0; e < n_local; ++e) {
     const int lo = expert_offsets[e], hi = expert_offsets[e + 1];
-    const int n256 = row_blocks(hi - lo).n256;
+    const int n256 = row_blocks(hi - lo, p.pad_low).n256;
     const int first = min(hi, lo + min(max(p.keep_rb - before, 0), n256) * 256);
     if (i < base + hi - first) return first + i - base;
     base += hi - first;

@@ -82,7 +82,7 @@ def test_down_projection_slices_follow_the_routing():
     counts = (1030, 1000, 1100, 1024, 960, 1090, 1020, 968)
     info = B.moe_debug_down_slices(_offsets(counts), 8192, full)
     assert info[:2] == (32, 5)
-    assert info[2] == sum(c % 256 for c in counts if c % 256 <= (128 if c >= 256 else 192)) and info[3] == 4096
+    assert info[2] == sum(c % 256 for c in counts if c % 256 <= 128) and info[3] == 4096
     with pytest.raises(B.MoeError):
         B.moe_debug_down_slices([0, 5, 3], cap, ep4)
     with pytest.raises(B.MoeError):
@@ -115,7 +115,12 @@ def test_sliced_work_list_covers_every_tile_and_slice_once(E_loc, hidden, inter,
             assert slices == 1
         n_sliced_cases += slices > 1
         # ordinal of every 256-row block, experts in order
-        first_rb = np.concatenate([[0], np.cumsum([(c // 256) + (c % 256 > (128 if c >= 256 else 192)) for c in counts])])
+        def blocks(c, pad_low):
+            pad = 128 if (c >= 256 or pad_low) else 192
+            r = c % 256
+            return c // 256 + (r > pad), int(64 < r <= pad) + int(0 < r <= 64 or 128 < r <= pad)
+        pad_low = sum(sum(blocks(c, False)) for c in counts) * ncb >= 256     # the launch fills the chip
+        first_rb = np.concatenate([[0], np.cumsum([blocks(c, pad_low)[0] for c in counts])])
         seen = {}
         scratch_cells = set()
         for h, e, r0, nb, z, kt0, n, srow in units:

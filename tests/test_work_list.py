@@ -69,6 +69,22 @@ def test_remainder_tiles_and_padding():
         assert h.sum() - rows < (64 if r <= pad else 128)
 
 
+def test_experts_below_256_rows_are_padded_only_in_launches_that_fill_the_chip():
+    rows = np.array([150, 190, 130, 100, 60, 193, 170, 129])
+    few, _ = _check_cover(rows, int(rows.sum()), 2)       # 2 column blocks: 26 tiles in all
+    many, _ = _check_cover(rows, int(rows.sum()), 112)    # 112 column blocks: 1456 tiles
+    def heights(units, expert):
+        return sorted(int(h) for h, e, _, _, nb in units if h and e == expert and nb == 0)
+    for e, r in enumerate(rows):
+        want_few = [256] if r > 192 else ([64, 128] if r > 128 else ([128] if r > 64 else [64]))
+        want_many = [256] if r > 128 else ([128] if r > 64 else [64])
+        assert heights(few, e) == want_few and heights(many, e) == want_many, (e, r)
+    # the switch is at 256 tiles counted before any such padding
+    rows = np.array([150] * 8)                            # 16 row blocks
+    assert (np.asarray(_check_cover(rows, 1200, 15)[0])[:, 0] == 256).sum() == 0      # 240 tiles
+    assert (np.asarray(_check_cover(rows, 1200, 16)[0])[:, 0] == 256).sum() == 8 * 16  # 256 tiles
+
+
 def test_full_tiles_first_and_balanced_over_xcds():
     # 8 experts of about 1024 rows, 112 column blocks (the GEMM1 shape of an 8 x 14336 layer)
     rows = np.array([1040, 1030, 1050, 1024, 1000, 1047, 1033, 1025])
