@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies, to scale FETCH_SIZE / WRITE_SIZE counters under rocprofv3")
+    ap.add_argument("--no-overlap-shared", action="store_true",
+                    help="run the shared expert after the routed experts instead of beside them on a second stream")
     ap.add_argument("--graph", choices=["auto", "on", "off"], default="auto",
                     help="replay the layer as one HIP graph (auto: when an eager step takes < 1 ms)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens the oracle is timed on (0 = auto)")
@@ -106,7 +108,7 @@ def main():
     t0 = time.time()
     li = I.make_layer_inputs(shape, T, args.seed)
     gen_s = time.time() - t0
-    layer = ExpertShardLayer.from_inputs(li)
+    layer = ExpertShardLayer.from_inputs(li, overlap_shared=not args.no_overlap_shared)
     x = bf16_tensor(li.x)
     logits = None if li.logits is None else torch.from_numpy(li.logits).cuda()
 

@@ -49,7 +49,7 @@ class ExpertShardLayer:
     def __init__(self, *, n_experts, top_k, hidden, inter_full, inter_slice, n_local_experts=None, expert_offset=0,
                  renorm=True, w_router=None, w_gate=None, w_up=None, w_down=None, shared=None, w_shared_gate=None,
                  inter_shared_full=0, inter_shared_slice=0, max_tokens=0, y_perm_bf16=False, out_f32=False,
-                 device="cuda"):
+                 overlap_shared=True, device="cuda"):
         n_local_experts = n_experts if n_local_experts is None else n_local_experts
         self.E, self.k, self.H = n_experts, top_k, hidden
         self.shard = B.make_shard(n_experts, n_local_experts, expert_offset, hidden, inter_full, inter_slice)
@@ -66,6 +66,10 @@ class ExpertShardLayer:
                                              padded)
         self.y_perm_bf16, self.out_f32 = y_perm_bf16, out_f32
         self.device = device
+        # the shared expert depends on x only: it may run on a second stream (default priority) beside
+        # routing, permutation and the routed experts, and joins before the combine
+        self.overlap_shared = bool(overlap_shared) and shared is not None
+        self._side = torch.cuda.Stream(device=device) if self.overlap_shared else None
         self.Tmax = -1
         if max_tokens:
             self._alloc(max_tokens)
@@ -112,22 +116,33 @@ class ExpertShardLayer:
         if logits is not None:
             self.logits[:T].copy_(logits)
             flags |= B.MOE_LOGITS_GIVEN
-        B.moe_route_topk(x, self.w_router, self.logits, T, H, E, k, flags, self.topk_idx, self.topk_w, stream)
-        B.moe_permute(x, self.topk_idx, T, k, self.shard, self.x_perm, self.expert_offsets, self.row_src,
-                      self.slot_row, self.workspace, stream=stream)
         yflag = B.MOE_Y_PERM_BF16 if self.y_perm_bf16 else 0
-        B.moe_expert_ffn(self.x_perm, self.expert_offsets, T * k, self.ffn_shard, self.w_gate, self.w_up, self.w_down,
-                         self.h_ws, self.y_perm, self.ffn_ws, yflag, stream)
-        y_shared = None
+        y_shared, joined = None, None
         if self.shared is not None:
             if getattr(self, "_sh_T", None) != T:
                 if torch.cuda.is_current_stream_capturing():
                     raise RuntimeError("run one eager forward with this token count before capturing a graph")
                 self.sh_offsets.copy_(torch.tensor([0, T], dtype=torch.int32))
                 self._sh_T = T
+            y_shared = self.y_shared
+        if self.shared is not None and self.overlap_shared:
+            if stream is not None:
+                raise ValueError("overlap_shared works on torch's current stream only")
+            main = torch.cuda.current_stream()
+            self._side.wait_stream(main)          # x (and sh_offsets) are ready where main stands now
+            B.moe_expert_ffn(x, self.sh_offsets, T, self.shared_shard, self.shared[0], self.shared[1], self.shared[2],
+                             self.h_sh, self.y_shared, self.ffn_ws_sh, yflag, self._side)
+            joined = self._side
+        B.moe_route_topk(x, self.w_router, self.logits, T, H, E, k, flags, self.topk_idx, self.topk_w, stream)
+        B.moe_permute(x, self.topk_idx, T, k, self.shard, self.x_perm, self.expert_offsets, self.row_src,
+                      self.slot_row, self.workspace, stream=stream)
+        B.moe_expert_ffn(self.x_perm, self.expert_offsets, T * k, self.ffn_shard, self.w_gate, self.w_up, self.w_down,
+                         self.h_ws, self.y_perm, self.ffn_ws, yflag, stream)
+        if self.shared is not None and not self.overlap_shared:
             B.moe_expert_ffn(x, self.sh_offsets, T, self.shared_shard, self.shared[0], self.shared[1], self.shared[2],
                              self.h_sh, self.y_shared, self.ffn_ws_sh, yflag, stream)
-            y_shared = self.y_shared
+        if joined is not None:
+            torch.cuda.current_stream().wait_stream(joined)
         cflags = yflag | (B.MOE_OUT_F32 if self.out_f32 else 0)
         gate_x = x if self.w_shared_gate is not None else None
         B.moe_combine(self.y_perm, self.slot_row, self.topk_w, T, k, H, y_shared, gate_x, self.w_shared_gate,

@@ -352,12 +352,27 @@ def test_layer_ep_shards_and_union_invariant(ep):
     assert (idx < 8 // ep).sum() > (idx >= 8 - 8 // ep).sum()
 
 
+@pytest.mark.parametrize("overlap", [True, False])
 @pytest.mark.parametrize("T", [32, 500])
-def test_layer_qwen_like_with_shared_expert(T):
+def test_layer_qwen_like_with_shared_expert(T, overlap):
     li = I.make_layer_inputs(SMALL_QWEN, T, 0)
-    layer, y = _run_layer(li)
+    layer, y = _run_layer(li, overlap_shared=overlap)
     ref = _oracle_layer(li, _check_integers(layer, li, T))
     assert _rel(y, ref) < REL_L2 and np.abs(y - ref).max() < MAX_ABS
+    # the shared expert may run beside the routed ones on a second stream: repeated calls and
+    # replays of a captured graph, with eager work in between, must give the same bits
+    x = bf16_tensor(li.x)
+    first = layer.forward(x).clone()
+    for _ in range(3):
+        assert torch.equal(layer.forward(x), first)
+    graph, out = layer.capture(x)
+    for _ in range(3):
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, first)
+        layer.forward(x)
+        torch.cuda.synchronize()
 
 
 def test_layer_hybrid_ep_tp_shard():
