@@ -29,8 +29,8 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 # (FETCH_SIZE, WRITE_SIZE in KiB per dispatch; see profiles/<workload>_rocprofv3.txt), each scaled by
 # what the same counter reads for a plain 1 GiB device copy: FETCH_SIZE x 2.0, WRITE_SIZE x 1.0.
 MEASURED_TRAFFIC_BYTES = {
-    "mixtral_prefill": (1958893.3 * 2.0 + 232964.0) * 1024,
-    "mixtral_decode": (935100.6 * 2.0 + 898.3) * 1024,
+    "mixtral_prefill": (1958653.6 * 2.0 + 232964.2) * 1024,
+    "mixtral_decode": (935096.4 * 2.0 + 898.4) * 1024,
 }
 
 # name -> (inputs.WORKLOADS key, token count, description)
