@@ -123,10 +123,11 @@ __device__ inline TileCoord wave_locate(const WaveRouting& w, const int (&mbs)[k
   if (!h.found) return t;
   const int m = wave_pick(mbs, h), lo = wave_pick(w.lo, h);
   const int local = idx - wave_pick(pre, h) * n_col_blocks;
-  t.expert = h.lane + 64 * h.j;
-  t.nb = local / m;
-  t.row0 = lo + wave_pick(base, h) + (local % m) * 256;
-  t.row_end = lo + wave_pick(w.rows, h);
+  // (the values are uniform by construction; reading them from the first lane tells the compiler so)
+  t.expert = __builtin_amdgcn_readfirstlane(h.lane + 64 * h.j);
+  t.nb = __builtin_amdgcn_readfirstlane(local / m);
+  t.row0 = __builtin_amdgcn_readfirstlane(lo + wave_pick(base, h) + (local % m) * 256);
+  t.row_end = __builtin_amdgcn_readfirstlane(lo + wave_pick(w.rows, h));
   return t;
 }
 
