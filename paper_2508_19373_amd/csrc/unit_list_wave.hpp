@@ -17,13 +17,17 @@ namespace gg {
 
 constexpr int kLaneChunks = 4;  // 256 experts / 64 lanes
 
+// Inclusive prefix sum over the 64 lanes with data-parallel-primitive moves (a few cycles each,
+// against a round trip through the LDS crossbar per step of a shuffle-based scan): shifts by 1, 2,
+// 4, 8 inside each row of 16 lanes (lanes shifted in from outside the row read 0), then lane 15 of
+// rows 0 and 2 is broadcast into rows 1 and 3, then lane 31 into rows 2 and 3.
 __device__ inline int wave_incl_scan(int v) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const int t = __shfl_up(v, d);
-    if (lane >= d) v += t;
-  }
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, false);  // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, false);  // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, false);  // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, false);  // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);  // row_bcast:15 into rows 1, 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);  // row_bcast:31 into rows 2, 3
   return v;
 }
 
