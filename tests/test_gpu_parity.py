@@ -193,6 +193,41 @@ def test_expert_ffn_against_oracle(H, I_s, counts):
     assert _rel(yb[:R], ref) < REL_L2
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_expert_ffn_random_shapes(seed):
+    # seeded random shards: which kernels run, how rows are cut into tiles and what is cut along K
+    # all follow from the shape and the routing, so this walks through the combinations
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.integers(1, 13))
+    E = n * int(rng.choice([1, 1, 2, 4]))
+    H = 64 * int(rng.integers(1, 17))
+    I_s = 64 * int(rng.integers(1, 33))
+    kind = seed % 4
+    if kind == 0:      # decode-sized
+        counts = rng.integers(0, 40, n)
+    elif kind == 1:    # around the tile heights
+        counts = rng.choice([0, 1, 63, 64, 65, 127, 128, 129, 191, 192, 193, 255, 256, 257, 300, 520], n)
+    elif kind == 2:    # one hot expert
+        counts = rng.integers(0, 30, n)
+        counts[int(rng.integers(0, n))] = int(rng.integers(300, 1500))
+    else:
+        counts = rng.multinomial(int(rng.integers(200, 2500)), rng.dirichlet(np.ones(n)))
+    counts = [int(c) for c in counts]
+    wg, wu, wd = I.make_expert_weights(seed, I.MoEShape("f", H, n, 1, I_s, True))
+    offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    R = int(offs[-1])
+    cap = R + int(rng.integers(0, 2000)) if E > n else R + int(rng.integers(0, 9))
+    cap = max(cap, 1)
+    xp = I.make_x(seed + 1, cap, H)
+    shard = B.make_shard(E, n, 0, H, I_s, I_s)
+    y = _ffn_gpu(xp, offs, shard, wg, wu, wd)
+    assert np.all(np.isnan(y[R:])), "rows past R must not be written"
+    if R:
+        ref = O.expert_ffn(xp[:R], offs, wg, wu, wd)
+        assert _rel(y[:R], ref) < REL_L2, (n, E, H, I_s, counts, cap)
+        assert np.abs(y[:R] - ref).max() < MAX_ABS, (n, E, H, I_s, counts, cap)
+
+
 @pytest.mark.parametrize("H,I_s,counts,E,slices", [
     # slices = (256-row blocks whose tiles run whole, K slices of every other tile)
     (512, 4096, [300, 10], 8, (0, 8)),          # 3 row blocks x 2 column blocks: every tile in 8 K slices
