@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies, to scale FETCH_SIZE / WRITE_SIZE counters under rocprofv3")
+    ap.add_argument("--permuted-copy", action="store_true",
+                    help="moe_permute writes x_perm and moe_expert_ffn reads it (default: the FFN gathers rows of x)")
     ap.add_argument("--no-overlap-shared", action="store_true",
                     help="run the shared expert after the routed experts instead of beside them on a second stream")
     ap.add_argument("--graph", choices=["auto", "on", "off"], default="auto",
@@ -108,7 +110,8 @@ def main():
     t0 = time.time()
     li = I.make_layer_inputs(shape, T, args.seed)
     gen_s = time.time() - t0
-    layer = ExpertShardLayer.from_inputs(li, overlap_shared=not args.no_overlap_shared)
+    layer = ExpertShardLayer.from_inputs(li, overlap_shared=not args.no_overlap_shared,
+                                         gather_in_ffn=not args.permuted_copy)
     x = bf16_tensor(li.x)
     logits = None if li.logits is None else torch.from_numpy(li.logits).cuda()
 
@@ -146,8 +149,13 @@ def main():
     br["permute"] = time_events(lambda: B.moe_permute(x, layer.topk_idx, T, k, layer.shard, layer.x_perm,
                                                       layer.expert_offsets, layer.row_src, layer.slot_row,
                                                       layer.workspace), it, torch)
-    ffn = lambda fl: B.moe_expert_ffn(layer.x_perm, layer.expert_offsets, T * k, layer.shard, layer.w_gate,
-                                      layer.w_up, layer.w_down, layer.h_ws, layer.y_perm, layer.ffn_ws, fl)
+    if layer.gather_in_ffn:   # the routed experts read their rows of x in place
+        ffn = lambda fl: B.moe_expert_ffn_gather(x, layer.row_src, k, layer.expert_offsets, T * k, layer.shard,
+                                                 layer.w_gate, layer.w_up, layer.w_down, layer.h_ws, layer.y_perm,
+                                                 layer.ffn_ws, fl)
+    else:
+        ffn = lambda fl: B.moe_expert_ffn(layer.x_perm, layer.expert_offsets, T * k, layer.shard, layer.w_gate,
+                                          layer.w_up, layer.w_down, layer.h_ws, layer.y_perm, layer.ffn_ws, fl)
     br["ffn_gateup_swiglu"] = time_events(lambda: ffn(B.MOE_FFN_SKIP_DOWN), it, torch)
     br["ffn_down"] = time_events(lambda: ffn(B.MOE_FFN_SKIP_GATEUP), it, torch)
     if layer.shared is not None:

@@ -95,9 +95,11 @@ int moe_route_topk(const void* x_bf16, const float* w_router, float* logits,
  * Token permutation by expert (the "dispatch" of the Top-K mechanism, restricted to the
  * experts this shard holds): a stable counting sort of the local assignments a = t*k + j by
  * expert id.
- * x_bf16         [T,H] bf16
+ * x_bf16         [T,H] bf16      (unused, may be NULL, when x_perm is NULL)
  * topk_idx       [T,k] int32 global expert ids (each in [0,E))
- * x_perm         [T*k,H] bf16  rows [0,R) written (row r = x[row_src[r] / k]); rest untouched
+ * x_perm         [T*k,H] bf16  rows [0,R) written (row r = x[row_src[r] / k]); rest untouched.
+ *                NULL: only the index arrays are computed, for moe_expert_ffn_gather, which
+ *                reads the rows of x in place
  * expert_offsets [E_loc+1] int32  exclusive prefix sum of local rows per expert; last = R
  * row_src        [T*k] int32   assignment id of each permuted row, rows [0,R) written
  * slot_row       [T*k] int32   permuted row of each assignment, -1 if its expert is not local
@@ -131,6 +133,18 @@ int moe_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int32_t ca
                    const moe_shard_t* shard, const void* w_gate, const void* w_up,
                    const void* w_down, void* h_workspace, void* y_perm,
                    void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
+
+/*
+ * moe_expert_ffn without the permuted copy of the activations: row r of the first GEMM's input is
+ * x_bf16[row_src[r] / k] (row_src as moe_permute writes it, k the Top-K width), read where it lies.
+ * Saves writing and re-reading x_perm (2 * R * H * 2 bytes per layer); everything else as above.
+ * x_bf16 [T,H] bf16, row_src [>= R] int32 (device), 1 <= k <= MOE_MAX_TOPK.
+ */
+int moe_expert_ffn_gather(const void* x_bf16, const int32_t* row_src, int32_t k,
+                          const int32_t* expert_offsets, int32_t cap_rows, const moe_shard_t* shard,
+                          const void* w_gate, const void* w_up, const void* w_down, void* h_workspace,
+                          void* y_perm, void* workspace, size_t workspace_bytes, uint32_t flags,
+                          void* stream);
 
 /*
  * Weighted un-permute / combine of the Top-K expert outputs, plus the shared expert:

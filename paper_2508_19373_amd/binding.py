@@ -25,7 +25,7 @@ MOE_FFN_SKIP_DOWN = 1 << 5
 MOE_MAX_EXPERTS = 256
 MOE_MAX_TOPK = 16
 
-EXPORTS = ("moe_route_topk", "moe_permute", "moe_expert_ffn", "moe_combine", "moe_workspace_bytes",
+EXPORTS = ("moe_route_topk", "moe_permute", "moe_expert_ffn", "moe_expert_ffn_gather", "moe_combine", "moe_workspace_bytes",
            "moe_ffn_workspace_bytes", "moe_status_string")
 DEBUG_EXPORTS = ("moe_debug_gemm_units", "moe_debug_ffn_plan", "moe_debug_down_slices", "moe_debug_device_units")
 INT4_EXPORTS = ("moe_int4_dequantize", "moe_int4_quantize")
@@ -62,6 +62,8 @@ def lib() -> ctypes.CDLL:
         L.moe_permute.restype = ctypes.c_int
         L.moe_expert_ffn.argtypes = [vp, vp, i32, shp, vp, vp, vp, vp, vp, vp, sz, u32, vp]
         L.moe_expert_ffn.restype = ctypes.c_int
+        L.moe_expert_ffn_gather.argtypes = [vp, vp, i32, vp, i32, shp, vp, vp, vp, vp, vp, vp, sz, u32, vp]
+        L.moe_expert_ffn_gather.restype = ctypes.c_int
         L.moe_combine.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, u32, vp]
         L.moe_combine.restype = ctypes.c_int
         L.moe_workspace_bytes.argtypes = [i32, i32, shp]
@@ -146,6 +148,15 @@ def moe_expert_ffn(x_perm, expert_offsets, cap_rows, shard: MoeShard, w_gate, w_
     _check("moe_expert_ffn", lib().moe_expert_ffn(_ptr(x_perm), _ptr(expert_offsets), cap_rows, ctypes.byref(shard),
                                                   _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(h_workspace),
                                                   _ptr(y_perm), _ptr(workspace), wbytes, flags, _stream(stream)))
+
+
+def moe_expert_ffn_gather(x, row_src, k, expert_offsets, cap_rows, shard: MoeShard, w_gate, w_up, w_down, h_workspace,
+                          y_perm, workspace=None, flags=0, stream=None):
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check("moe_expert_ffn_gather",
+           lib().moe_expert_ffn_gather(_ptr(x), _ptr(row_src), k, _ptr(expert_offsets), cap_rows, ctypes.byref(shard),
+                                       _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(h_workspace), _ptr(y_perm),
+                                       _ptr(workspace), wbytes, flags, _stream(stream)))
 
 
 def moe_combine(y_perm, slot_row, topk_w, T, k, H, y_shared, x, w_shared_gate, y_out, flags=0, stream=None):

@@ -64,9 +64,9 @@ int moe_permute(const void* x_bf16, const int32_t* topk_idx, int32_t T, int32_t 
   if (st != MOE_OK) return st;
   if (T < 0 || k < 1 || k > MOE_MAX_TOPK || k > shard->n_experts) return MOE_ERR_INVALID_ARG;
   if ((int64_t)T * k >= (1 << 24)) return MOE_ERR_INVALID_ARG;
-  if (x_bf16 == nullptr || topk_idx == nullptr || x_perm == nullptr || expert_offsets == nullptr ||
-      row_src == nullptr || slot_row == nullptr)
+  if (topk_idx == nullptr || expert_offsets == nullptr || row_src == nullptr || slot_row == nullptr)
     return MOE_ERR_INVALID_ARG;
+  if (x_perm != nullptr && x_bf16 == nullptr) return MOE_ERR_INVALID_ARG;  // x is read only to fill x_perm
   if (shard->hidden % 8 != 0) return MOE_ERR_UNSUPPORTED_SHAPE;
   if (!aligned16(x_bf16) || !aligned16(x_perm)) return MOE_ERR_INVALID_ARG;
   if (workspace == nullptr || workspace_bytes < moe_workspace_bytes(T, k, shard)) return MOE_ERR_WORKSPACE;
@@ -75,26 +75,43 @@ int moe_permute(const void* x_bf16, const int32_t* topk_idx, int32_t T, int32_t 
                                         static_cast<hipStream_t>(stream)));
 }
 
-int moe_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int32_t cap_rows, const moe_shard_t* shard,
-                   const void* w_gate, const void* w_up, const void* w_down, void* h_workspace, void* y_perm,
-                   void* workspace, size_t workspace_bytes, uint32_t flags, void* stream) {
+static int expert_ffn_common(const void* x, moe::RowMap rows, const int32_t* expert_offsets, int32_t cap_rows,
+                             const moe_shard_t* shard, const void* w_gate, const void* w_up, const void* w_down,
+                             void* h_workspace, void* y_perm, void* workspace, size_t workspace_bytes, uint32_t flags,
+                             void* stream) {
   const int st = shard_status(shard);
   if (st != MOE_OK) return st;
   if (cap_rows < 0 || (flags & ~(uint32_t)(MOE_Y_PERM_BF16 | MOE_FFN_SKIP_GATEUP | MOE_FFN_SKIP_DOWN)))
     return MOE_ERR_INVALID_ARG;
-  if (x_perm == nullptr || expert_offsets == nullptr || w_gate == nullptr || w_up == nullptr ||
+  if (x == nullptr || expert_offsets == nullptr || w_gate == nullptr || w_up == nullptr ||
       w_down == nullptr || h_workspace == nullptr || y_perm == nullptr)
     return MOE_ERR_INVALID_ARG;
   if (shard->hidden % 64 != 0 || shard->inter_slice % 64 != 0) return MOE_ERR_UNSUPPORTED_SHAPE;
-  if (!aligned16(x_perm) || !aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down) ||
+  if (!aligned16(x) || !aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down) ||
       !aligned16(h_workspace) || !aligned16(y_perm))
     return MOE_ERR_INVALID_ARG;
   const size_t need = moe_ffn_workspace_bytes(cap_rows, shard);
   if (need > 0 && (workspace == nullptr || workspace_bytes < need || !aligned16(workspace))) return MOE_ERR_WORKSPACE;
-  return hip_status(moe::launch_expert_ffn(x_perm, expert_offsets, cap_rows, moe::expected_rows(cap_rows, shard),
+  return hip_status(moe::launch_expert_ffn(x, rows, expert_offsets, cap_rows, moe::expected_rows(cap_rows, shard),
                                            shard->n_local_experts, shard->hidden,
                                            shard->inter_slice, w_gate, w_up, w_down, h_workspace, y_perm, workspace,
                                            workspace_bytes, flags, static_cast<hipStream_t>(stream)));
+}
+
+int moe_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int32_t cap_rows, const moe_shard_t* shard,
+                   const void* w_gate, const void* w_up, const void* w_down, void* h_workspace, void* y_perm,
+                   void* workspace, size_t workspace_bytes, uint32_t flags, void* stream) {
+  return expert_ffn_common(x_perm, moe::RowMap{nullptr, 1}, expert_offsets, cap_rows, shard, w_gate, w_up, w_down,
+                           h_workspace, y_perm, workspace, workspace_bytes, flags, stream);
+}
+
+int moe_expert_ffn_gather(const void* x_bf16, const int32_t* row_src, int32_t k, const int32_t* expert_offsets,
+                          int32_t cap_rows, const moe_shard_t* shard, const void* w_gate, const void* w_up,
+                          const void* w_down, void* h_workspace, void* y_perm, void* workspace,
+                          size_t workspace_bytes, uint32_t flags, void* stream) {
+  if (row_src == nullptr || k < 1 || k > MOE_MAX_TOPK) return MOE_ERR_INVALID_ARG;
+  return expert_ffn_common(x_bf16, moe::RowMap{row_src, k}, expert_offsets, cap_rows, shard, w_gate, w_up, w_down,
+                           h_workspace, y_perm, workspace, workspace_bytes, flags, stream);
 }
 
 int moe_combine(const void* y_perm, const int32_t* slot_row, const float* topk_w, int32_t T, int32_t k, int32_t H,

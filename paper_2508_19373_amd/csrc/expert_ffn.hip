@@ -24,7 +24,7 @@ namespace {
 
 // Prefill-sized groups: LDS-DMA kernel, 256-column tiles of 256 / 128 / 64 rows.
 template <int BN>
-hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, int cap_rows, int est_rows, int n_local, int H,
+hipError_t launch_pair_dlds(const void* x_perm, RowMap rows, const int32_t* expert_offsets, int cap_rows, int est_rows, int n_local, int H,
                             int I_s, const void* w_gate, const void* w_up, const void* w_down, void* h_ws,
                             void* y_perm, void* workspace, uint32_t flags, hipStream_t stream) {
   const bool y_bf16 = (flags & MOE_Y_PERM_BF16) != 0;
@@ -36,7 +36,7 @@ hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, i
     const int ncb = (I_s + BN / 2 - 1) / (BN / 2);
     hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, true, uint16_t, false>), grid_for(ncb), block, 0, stream, xp,
                        expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_gate),
-                       static_cast<const uint16_t*>(w_up), I_s, H, hw, ncb, static_cast<uint16_t*>(nullptr), 0);
+                       static_cast<const uint16_t*>(w_up), I_s, H, hw, ncb, static_cast<uint16_t*>(nullptr), 0, rows);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
   }
@@ -46,7 +46,7 @@ hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, i
     hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, uint16_t, false>), grid_for(ncb), block, 0, stream, hw,
                        expert_offsets, n_local, cap_rows, static_cast<const uint16_t*>(w_down),
                        static_cast<const uint16_t*>(nullptr), H, I_s, static_cast<uint16_t*>(y_perm), ncb,
-                       static_cast<uint16_t*>(nullptr), 0);
+                       static_cast<uint16_t*>(nullptr), 0, RowMap{nullptr, 1});
     return hipGetLastError();
   }
   const gg::SlicePlan sp = workspace == nullptr ? gg::SlicePlan{1, 0} : gg::slice_plan(cap_rows, ncb, I_s);
@@ -56,12 +56,13 @@ hipError_t launch_pair_dlds(const void* x_perm, const int32_t* expert_offsets, i
   if (sp.max_slices == 1) {
     hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, float, false>), grid_for(ncb), block, 0, stream, hw,
                        expert_offsets, n_local, cap_rows, wd, static_cast<const uint16_t*>(nullptr), H, I_s, yp, ncb,
-                       static_cast<float*>(nullptr), 0);
+                       static_cast<float*>(nullptr), 0, RowMap{nullptr, 1});
     return hipGetLastError();
   }
   hipLaunchKernelGGL((gg::grouped_gemm_dlds_kernel<BN, false, float, true>),
                      dim3(gg::sliced_grid(cap_rows, n_local, ncb)), block, 0, stream, hw, expert_offsets, n_local,
-                     cap_rows, wd, static_cast<const uint16_t*>(nullptr), H, I_s, ws, ncb, yp, sp.max_slices);
+                     cap_rows, wd, static_cast<const uint16_t*>(nullptr), H, I_s, ws, ncb, yp, sp.max_slices,
+                     RowMap{nullptr, 1});
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   hipLaunchKernelGGL(gg::sum_sliced_kernel, dim3(192, (H + 1023) / 1024), dim3(256), 0, stream, ws, expert_offsets, n_local, ncb,
@@ -76,7 +77,7 @@ constexpr int kWalkSlots = 512;  // 8-wavefront workgroups resident at once with
 
 template <int MT, bool GATEUP>
 bool launch_walk(const gw::WalkPlan& plan, const uint16_t* A, const int32_t* expert_offsets, int n_local,
-                 const uint16_t* Wa, const uint16_t* Wb, int n_out, int K, void* C, int cap_rows,
+                 const uint16_t* Wa, const uint16_t* Wb, int n_out, int K, void* C, int cap_rows, RowMap rows,
                  hipStream_t stream) {
   const int total_strips = n_out / 16;
   int chunks = (MT == 1 && plan.nw < 16 ? kWalkSlots : kWalkSlots / 2) / (n_local * plan.slices);
@@ -86,7 +87,7 @@ bool launch_walk(const gw::WalkPlan& plan, const uint16_t* A, const int32_t* exp
 #define MOE_WALK(NW, ST)                                                                                        \
   if (plan.nw == NW && plan.steps == ST) {                                                                      \
     hipLaunchKernelGGL((gw::grouped_walk_kernel<NW, ST, MT, GATEUP>), grid, dim3(NW * 64), 0, stream, A,        \
-                       expert_offsets, Wa, Wb, n_out, K, C, spw, cap_rows);                                     \
+                       expert_offsets, Wa, Wb, n_out, K, C, spw, cap_rows, rows);                               \
     return true;                                                                                                \
   }
   if constexpr (MT == 1) {
@@ -113,7 +114,7 @@ bool launch_walk(const gw::WalkPlan& plan, const uint16_t* A, const int32_t* exp
 }
 
 template <int MT>
-hipError_t launch_pair_decode(const void* x_perm, const int32_t* expert_offsets, int cap_rows, int n_local, int H,
+hipError_t launch_pair_decode(const void* x_perm, RowMap rows, const int32_t* expert_offsets, int cap_rows, int n_local, int H,
                               int I_s, const void* w_gate, const void* w_up, const void* w_down, void* h_ws,
                               void* y_perm, void* workspace, uint32_t flags, hipStream_t stream) {
   const bool y_bf16 = (flags & MOE_Y_PERM_BF16) != 0;
@@ -125,12 +126,12 @@ hipError_t launch_pair_decode(const void* x_perm, const int32_t* expert_offsets,
     bool done = false;
     if (p1.nw != 0 && p1.slices == 1 && I_s % 16 == 0)
       done = launch_walk<MT, true>(p1, xp, expert_offsets, n_local, static_cast<const uint16_t*>(w_gate),
-                                   static_cast<const uint16_t*>(w_up), I_s, H, hw, cap_rows, stream);
+                                   static_cast<const uint16_t*>(w_up), I_s, H, hw, cap_rows, rows, stream);
     if (!done) {
       const dim3 grid((I_s + gs::kStripN - 1) / gs::kStripN, n_local);
       hipLaunchKernelGGL((gs::grouped_stream_kernel<MT, true, uint16_t>), grid, dim3(gs::kWaves * 64), 0, stream, xp,
                          expert_offsets, static_cast<const uint16_t*>(w_gate), static_cast<const uint16_t*>(w_up),
-                         I_s, H, hw);
+                         I_s, H, hw, rows);
     }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
@@ -140,7 +141,7 @@ hipError_t launch_pair_decode(const void* x_perm, const int32_t* expert_offsets,
   if (!y_bf16 && p2.nw != 0 && H % 16 == 0 && (p2.slices == 1 || workspace != nullptr)) {
     void* out = p2.slices == 1 ? y_perm : workspace;
     if (launch_walk<MT, false>(p2, hw, expert_offsets, n_local, static_cast<const uint16_t*>(w_down),
-                               static_cast<const uint16_t*>(nullptr), H, I_s, out, cap_rows, stream)) {
+                               static_cast<const uint16_t*>(nullptr), H, I_s, out, cap_rows, RowMap{nullptr, 1}, stream)) {
       hipError_t err = hipGetLastError();
       if (err != hipSuccess || p2.slices == 1) return err;
       hipLaunchKernelGGL(gw::sum_slices_kernel, dim3(64), dim3(256), 0, stream, static_cast<const float*>(workspace),
@@ -152,11 +153,11 @@ hipError_t launch_pair_decode(const void* x_perm, const int32_t* expert_offsets,
   if (y_bf16)
     hipLaunchKernelGGL((gs::grouped_stream_kernel<MT, false, uint16_t>), grid, dim3(gs::kWaves * 64), 0, stream, hw,
                        expert_offsets, static_cast<const uint16_t*>(w_down), static_cast<const uint16_t*>(nullptr),
-                       H, I_s, static_cast<uint16_t*>(y_perm));
+                       H, I_s, static_cast<uint16_t*>(y_perm), RowMap{nullptr, 1});
   else
     hipLaunchKernelGGL((gs::grouped_stream_kernel<MT, false, float>), grid, dim3(gs::kWaves * 64), 0, stream, hw,
                        expert_offsets, static_cast<const uint16_t*>(w_down), static_cast<const uint16_t*>(nullptr),
-                       H, I_s, static_cast<float*>(y_perm));
+                       H, I_s, static_cast<float*>(y_perm), RowMap{nullptr, 1});
   return hipGetLastError();
 }
 
@@ -232,9 +233,9 @@ void ffn_plan(int cap_rows, int est_rows, int n_local, int H, int I_s, int32_t o
   }
 }
 
-hipError_t launch_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int cap_rows, int est_rows, int n_local, int H,
-                             int I_s, const void* w_gate, const void* w_up, const void* w_down, void* h_ws,
-                             void* y_perm, void* workspace, size_t workspace_bytes, uint32_t flags,
+hipError_t launch_expert_ffn(const void* x_perm, RowMap rows, const int32_t* expert_offsets, int cap_rows, int est_rows,
+                             int n_local, int H, int I_s, const void* w_gate, const void* w_up, const void* w_down,
+                             void* h_ws, void* y_perm, void* workspace, size_t workspace_bytes, uint32_t flags,
                              hipStream_t stream) {
   (void)workspace_bytes;
   if (cap_rows == 0) return hipSuccess;
@@ -242,12 +243,12 @@ hipError_t launch_expert_ffn(const void* x_perm, const int32_t* expert_offsets, 
   const int mt = decode_mt(cap_rows, est_rows, n_local);
   auto run = [&](bool walk, uint32_t f) {
     if (!walk)
-      return launch_pair_dlds<256>(x_perm, expert_offsets, cap_rows, est_rows, n_local, H, I_s, w_gate, w_up, w_down,
+      return launch_pair_dlds<256>(x_perm, rows, expert_offsets, cap_rows, est_rows, n_local, H, I_s, w_gate, w_up, w_down,
                                    h_ws, y_perm, workspace, f, stream);
     if (mt == 1)
-      return launch_pair_decode<1>(x_perm, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,
+      return launch_pair_decode<1>(x_perm, rows, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,
                                    y_perm, workspace, f, stream);
-    return launch_pair_decode<2>(x_perm, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,
+    return launch_pair_decode<2>(x_perm, rows, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,
                                  y_perm, workspace, f, stream);
   };
   const bool walk1 = prefer_walk(cap_rows, est_rows, n_local, I_s, H, true),

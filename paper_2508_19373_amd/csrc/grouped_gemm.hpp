@@ -92,7 +92,7 @@ template <int BM, int BN, int WM, int WN, int NSA, int NSB, bool GATEUP, typenam
 __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, const uint16_t* __restrict__ A,
                                             int cap_rows, const uint16_t* __restrict__ B0,
                                             const uint16_t* __restrict__ B1, int n_out, int K, int kt0, int nk,
-                                            OutT* __restrict__ C) {
+                                            OutT* __restrict__ C, const RowMap rows = RowMap{nullptr, 1}) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 16, TN = BN / WN / 16;
   constexpr int A_INST = BM / 8 / NW, B_INST = BN / 8 / NW;
@@ -118,7 +118,9 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
     const int inst = j * NW + wave;
     const int r = inst * 8 + (lane >> 3);
     const int c = (lane & 7) ^ swz(r);
-    const int gr = min(row0 + r, cap_rows - 1);
+    // rows past the tile's expert are computed and dropped: they read any valid row (with a row
+    // map, the expert's last one: entries past the routed rows are not defined)
+    const int gr = rows.row_src ? rows(min(row0 + r, hi - 1)) : min(row0 + r, cap_rows - 1);
     a_src[j] = A + (size_t)gr * K + (size_t)kt0 * BK + c * 8;
   }
   const size_t expert_stride = (size_t)n_out * K;
@@ -334,7 +336,7 @@ template <int BN, bool GATEUP, typename OutT, bool SLICED>
 __global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
     const uint16_t* __restrict__ A, const int32_t* __restrict__ expert_offsets, int n_local, int cap_rows,
     const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1, int n_out, int K, OutT* __restrict__ C,
-    int n_col_blocks, OutT* __restrict__ y, int max_slices) {
+    int n_col_blocks, OutT* __restrict__ y, int max_slices, const RowMap rows) {
   __shared__ __attribute__((aligned(1024))) uint16_t smem[kLdsBytes / 2];
   int nk = K / BK, kt0 = 0, cls;
   OutT* out = C;
@@ -355,11 +357,11 @@ __global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
     if (!find_tile(expert_offsets, n_local, n_col_blocks, blockIdx.x, cls, tc)) return;
   }
   if (cls == 0)
-    gemm_tile<256, BN, 2, 2, 2, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out);
+    gemm_tile<256, BN, 2, 2, 2, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out, rows);
   else if (cls == 1)
-    gemm_tile<128, BN, 2, 2, 3, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out);
+    gemm_tile<128, BN, 2, 2, 3, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out, rows);
   else
-    gemm_tile<64, BN, 1, 4, 4, 4, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out);
+    gemm_tile<64, BN, 1, 4, 4, 4, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out, rows);
 }
 
 // y[r, :] += partial sums of slices 1, 2, ... in that order, for the rows the sliced kernel cut

@@ -35,7 +35,7 @@ __device__ __forceinline__ float silu_mul(float g, float u) { return g * __built
 template <int MT, bool GATEUP, typename OutT>
 __device__ __forceinline__ void stream_rows(float* red, const uint16_t* __restrict__ A, int row_lo, int row_hi,
                                             const uint16_t* __restrict__ Wa, const uint16_t* __restrict__ Wb,
-                                            int n0, int n_out, int K, OutT* __restrict__ C) {
+                                            int n0, int n_out, int K, OutT* __restrict__ C, const RowMap rows) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, kq = lane >> 4;
 
@@ -48,7 +48,7 @@ __device__ __forceinline__ void stream_rows(float* red, const uint16_t* __restri
 
   const uint16_t* a_ptr[MT];
 #pragma unroll
-  for (int t = 0; t < MT; ++t) a_ptr[t] = A + (size_t)min(row_lo + t * 16 + l16, row_hi - 1) * K + kq * 8;
+  for (int t = 0; t < MT; ++t) a_ptr[t] = A + (size_t)rows(min(row_lo + t * 16 + l16, row_hi - 1)) * K + kq * 8;
   const uint16_t* b_ptr = W + (size_t)min(n0 + l16, n_out - 1) * K + kq * 8;
 
   f32x4 acc[MT];
@@ -126,7 +126,7 @@ constexpr int kRedFloats = kWaves * kMaxMT * 256;  // 16 KB
 template <int MAXMT, bool GATEUP, typename OutT>
 __global__ __launch_bounds__(kWaves * 64) void grouped_stream_kernel(
     const uint16_t* __restrict__ A, const int32_t* __restrict__ expert_offsets, const uint16_t* __restrict__ Wa,
-    const uint16_t* __restrict__ Wb, int n_out, int K, OutT* __restrict__ C) {
+    const uint16_t* __restrict__ Wb, int n_out, int K, OutT* __restrict__ C, const RowMap rows) {
   __shared__ float red[kRedFloats];
   const int e = blockIdx.y;
   const int lo = expert_offsets[e], hi = expert_offsets[e + 1];
@@ -138,10 +138,10 @@ __global__ __launch_bounds__(kWaves * 64) void grouped_stream_kernel(
   const int M = hi - lo;
   if (MAXMT == 1 || M <= 16) {
     for (int m0 = lo; m0 < hi; m0 += 16)
-      stream_rows<1, GATEUP, OutT>(red, A, m0, min(m0 + 16, hi), wa, wb, n0, n_out, K, C);
+      stream_rows<1, GATEUP, OutT>(red, A, m0, min(m0 + 16, hi), wa, wb, n0, n_out, K, C, rows);
   } else {
     for (int m0 = lo; m0 < hi; m0 += 32)  // more than 32 rows: the strip is re-streamed per 32 rows
-      stream_rows<2, GATEUP, OutT>(red, A, m0, min(m0 + 32, hi), wa, wb, n0, n_out, K, C);
+      stream_rows<2, GATEUP, OutT>(red, A, m0, min(m0 + 32, hi), wa, wb, n0, n_out, K, C, rows);
   }
 }
 

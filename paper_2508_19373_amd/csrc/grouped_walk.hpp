@@ -55,7 +55,8 @@ constexpr int ring_size(int n) {
 template <int NW, int STEPS, int MT, bool GATEUP>
 __global__ __launch_bounds__(NW * 64, (MT == 1 ? 4 : 2)) void grouped_walk_kernel(
     const uint16_t* __restrict__ A, const int32_t* __restrict__ expert_offsets, const uint16_t* __restrict__ Wa,
-    const uint16_t* __restrict__ Wb, int n_out, int K, void* __restrict__ Cv, int strips_per_wg, int cap_rows) {
+    const uint16_t* __restrict__ Wb, int n_out, int K, void* __restrict__ Cv, int strips_per_wg, int cap_rows,
+    const RowMap rows) {
   constexpr int NB = GATEUP ? 2 : 1;
   constexpr int ITEMS = NB * STEPS;  // weight loads (1 KB each) per strip per wave
   // MT = 1 has 128 VGPRs: 4 * STEPS hold the activations, and a ring that does not fit next to them
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(NW * 64, (MT == 1 ? 4 : 2)) void grouped_walk_kerne
     bf16x8 a[STEPS][MT];
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
-      const uint16_t* ap = A + (size_t)min(m0 + t * 16 + l16, m_hi - 1) * K + kbase;
+      const uint16_t* ap = A + (size_t)rows(min(m0 + t * 16 + l16, m_hi - 1)) * K + kbase;
 #pragma unroll
       for (int s = 0; s < STEPS; ++s) a[s][t] = *reinterpret_cast<const bf16x8*>(ap + s * 32);
     }

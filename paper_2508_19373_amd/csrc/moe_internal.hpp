@@ -34,6 +34,14 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+// Where the rows of the first GEMM come from: row r of the input is x[row_src[r] / k] (the token of
+// assignment row_src[r]); row_src == nullptr means the input is already permuted (row r itself).
+struct RowMap {
+  const int32_t* row_src;
+  int k;
+  __host__ __device__ inline int operator()(int r) const { return row_src ? row_src[r] / k : r; }
+};
+
 // launchers (each returns hipGetLastError() after enqueueing on `stream`)
 hipError_t launch_route_topk(const void* x, const float* w_router, float* logits, int T, int H, int E, int k,
                              uint32_t flags, int32_t* topk_idx, float* topk_w, hipStream_t stream);
@@ -43,9 +51,10 @@ hipError_t launch_permute(const void* x, const int32_t* topk_idx, int T, int k, 
 size_t permute_workspace_bytes(int T, int k, int n_local);
 // est_rows: the rows this shard expects (cap_rows scaled by its share of the experts); it steers the
 // choice of kernels and K slices only, every bound is taken from cap_rows.
-hipError_t launch_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int cap_rows, int est_rows, int n_local, int H,
-                             int I_s, const void* w_gate, const void* w_up, const void* w_down, void* h_ws,
-                             void* y_perm, void* workspace, size_t workspace_bytes, uint32_t flags, hipStream_t stream);
+hipError_t launch_expert_ffn(const void* x_perm, RowMap rows, const int32_t* expert_offsets, int cap_rows, int est_rows,
+                             int n_local, int H, int I_s, const void* w_gate, const void* w_up, const void* w_down,
+                             void* h_ws, void* y_perm, void* workspace, size_t workspace_bytes, uint32_t flags,
+                             hipStream_t stream);
 size_t ffn_workspace_bytes(int cap_rows, int est_rows, int n_local, int H, int I_s);
 // What launch_expert_ffn would do: {GEMM1 by the walk kernel, GEMM2 by the walk kernel, rows per
 // walk pass / 16, K slices of GEMM2}.

@@ -225,7 +225,7 @@ hipError_t launch_permute(const void* x, const int32_t* topk_idx, int T, int k, 
   const int A = T * k;
   hipError_t err;
   if (A <= 2 * kIdxThreads) {  // small batch: one workgroup does it all in one launch
-    const bool fuse = (size_t)A * H * 2 <= (256u << 10);
+    const bool fuse = x_perm != nullptr && (size_t)A * H * 2 <= (256u << 10);
     hipLaunchKernelGGL(permute_index_kernel, dim3(1), dim3(kIdxThreads), 0, stream, topk_idx, A, n_local, offset,
                        expert_offsets, row_src, slot_row, fuse ? static_cast<const uint4*>(x) : nullptr, k, H / 8,
                        static_cast<uint4*>(x_perm));
@@ -241,7 +241,7 @@ hipError_t launch_permute(const void* x, const int32_t* topk_idx, int T, int k, 
                        slot_row);
     err = hipGetLastError();
   }
-  if (err != hipSuccess || A == 0) return err;
+  if (err != hipSuccess || A == 0 || x_perm == nullptr) return err;  // index only: the caller gathers on the fly
   const int grid = A < 8192 ? A : 8192;
   hipLaunchKernelGGL(gather_rows_kernel, dim3(grid), dim3(kGatherThreads), 0, stream,
                      static_cast<const uint4*>(x), row_src, expert_offsets, n_local, k, H / 8,

@@ -49,7 +49,7 @@ class ExpertShardLayer:
     def __init__(self, *, n_experts, top_k, hidden, inter_full, inter_slice, n_local_experts=None, expert_offset=0,
                  renorm=True, w_router=None, w_gate=None, w_up=None, w_down=None, shared=None, w_shared_gate=None,
                  inter_shared_full=0, inter_shared_slice=0, max_tokens=0, y_perm_bf16=False, out_f32=False,
-                 overlap_shared=True, device="cuda"):
+                 overlap_shared=True, gather_in_ffn=True, device="cuda"):
         n_local_experts = n_experts if n_local_experts is None else n_local_experts
         self.E, self.k, self.H = n_experts, top_k, hidden
         self.shard = B.make_shard(n_experts, n_local_experts, expert_offset, hidden, inter_full, inter_slice)
@@ -68,6 +68,8 @@ class ExpertShardLayer:
         self.device = device
         # the shared expert depends on x only: it may run on a second stream (default priority) beside
         # routing, permutation and the routed experts, and joins before the combine
+        # the routed experts read their rows of x in place through row_src (no permuted copy of x)
+        self.gather_in_ffn = bool(gather_in_ffn)
         self.overlap_shared = bool(overlap_shared) and shared is not None
         self._side = torch.cuda.Stream(device=device) if self.overlap_shared else None
         self.Tmax = -1
@@ -82,7 +84,7 @@ class ExpertShardLayer:
         self.logits = torch.empty((Tn, E), dtype=torch.float32, device=d)
         self.topk_idx = torch.empty((Tn, k), dtype=torch.int32, device=d)
         self.topk_w = torch.empty((Tn, k), dtype=torch.float32, device=d)
-        self.x_perm = torch.empty((cap, H), dtype=torch.bfloat16, device=d)
+        self.x_perm = None if self.gather_in_ffn else torch.empty((cap, H), dtype=torch.bfloat16, device=d)
         self.expert_offsets = torch.empty(self.shard.n_local_experts + 1, dtype=torch.int32, device=d)
         self.row_src = torch.empty(cap, dtype=torch.int32, device=d)
         self.slot_row = torch.empty(cap, dtype=torch.int32, device=d)
@@ -136,8 +138,12 @@ class ExpertShardLayer:
         B.moe_route_topk(x, self.w_router, self.logits, T, H, E, k, flags, self.topk_idx, self.topk_w, stream)
         B.moe_permute(x, self.topk_idx, T, k, self.shard, self.x_perm, self.expert_offsets, self.row_src,
                       self.slot_row, self.workspace, stream=stream)
-        B.moe_expert_ffn(self.x_perm, self.expert_offsets, T * k, self.ffn_shard, self.w_gate, self.w_up, self.w_down,
-                         self.h_ws, self.y_perm, self.ffn_ws, yflag, stream)
+        if self.gather_in_ffn:
+            B.moe_expert_ffn_gather(x, self.row_src, k, self.expert_offsets, T * k, self.ffn_shard, self.w_gate,
+                                    self.w_up, self.w_down, self.h_ws, self.y_perm, self.ffn_ws, yflag, stream)
+        else:
+            B.moe_expert_ffn(self.x_perm, self.expert_offsets, T * k, self.ffn_shard, self.w_gate, self.w_up,
+                             self.w_down, self.h_ws, self.y_perm, self.ffn_ws, yflag, stream)
         if self.shared is not None and not self.overlap_shared:
             B.moe_expert_ffn(x, self.sh_offsets, T, self.shared_shard, self.shared[0], self.shared[1], self.shared[2],
                              self.h_sh, self.y_shared, self.ffn_ws_sh, yflag, stream)

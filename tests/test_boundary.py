@@ -124,6 +124,9 @@ def test_permute_validation(lib):
     assert f(P, P, 1 << 23, 2, ctypes.byref(s), P, P, P, P, P, need, None) == B.MOE_ERR_INVALID_ARG
     s2 = _shard(hidden=12)
     assert f(P, P, 4, 2, ctypes.byref(s2), P, P, P, P, P, need, None) == B.MOE_ERR_UNSUPPORTED_SHAPE
+    # a permuted copy needs x; without one (index arrays only) x may be missing too
+    assert f(None, P, 4, 2, ctypes.byref(s), P, P, P, P, P, need, None) == B.MOE_ERR_INVALID_ARG
+    assert f(None, P, 4, 2, ctypes.byref(s), None, P, None, P, P, need, None) == B.MOE_ERR_INVALID_ARG   # row_src missing
 
 
 def test_expert_ffn_validation(lib):
@@ -149,6 +152,19 @@ def test_expert_ffn_validation(lib):
     assert B.moe_ffn_workspace_bytes(1024, one) == (65536 // 14) * 3584 * 4   # up to 16 slices, all but the first in scratch
     assert f(P, P, 32, ctypes.byref(mix), P, P, P, P, P, None, 0, 0, None) == B.MOE_ERR_WORKSPACE
     assert f(P, P, 32, ctypes.byref(mix), P, P, P, P, P, P, need - 1, 0, None) == B.MOE_ERR_WORKSPACE
+
+
+def test_expert_ffn_gather_validation(lib):
+    f = lib.moe_expert_ffn_gather
+    s = _shard()
+    W = 1 << 30
+    assert f(P, None, 2, P, 8, ctypes.byref(s), P, P, P, P, P, P, W, 0, None) == B.MOE_ERR_INVALID_ARG    # no row map
+    assert f(P, P, 0, P, 8, ctypes.byref(s), P, P, P, P, P, P, W, 0, None) == B.MOE_ERR_INVALID_ARG
+    assert f(P, P, 17, P, 8, ctypes.byref(s), P, P, P, P, P, P, W, 0, None) == B.MOE_ERR_INVALID_ARG
+    assert f(None, P, 2, P, 8, ctypes.byref(s), P, P, P, P, P, P, W, 0, None) == B.MOE_ERR_INVALID_ARG
+    assert f(P, P, 2, P, -1, ctypes.byref(s), P, P, P, P, P, P, W, 0, None) == B.MOE_ERR_INVALID_ARG
+    mix = _shard(hidden=4096, inter_full=14336, inter_slice=14336)
+    assert f(P, P, 2, P, 32, ctypes.byref(mix), P, P, P, P, P, None, 0, 0, None) == B.MOE_ERR_WORKSPACE
 
 
 def test_combine_validation(lib):

@@ -87,7 +87,14 @@ def test_full_size_against_oracle(key, T):
     assert np.array_equal(layer.expert_offsets.cpu().numpy(), offs)
     assert np.array_equal(layer.row_src[:R].cpu().numpy(), row_src)
     assert np.array_equal(layer.slot_row[:T * k].cpu().numpy(), slot_row)
-    assert np.array_equal(bf16_bits(layer.x_perm[:R]), x_perm)
+    # the layer's FFN reads its rows of x in place; the permuted copy is still part of moe_permute
+    xp = torch.empty((max(T * k, 1), shape.hidden), dtype=torch.bfloat16, device="cuda")
+    i32 = lambda n: torch.empty(n, dtype=torch.int32, device="cuda")
+    B.moe_permute(x, layer.topk_idx, T, k, layer.shard, xp, i32(shape.n_local_experts + 1), i32(T * k), i32(T * k),
+                  layer.workspace)
+    torch.cuda.synchronize()
+    assert np.array_equal(bf16_bits(xp[:R]), x_perm)
+    del xp
     if key == "mixtral_ep4_hot":
         assert R > 0.5 * T * k  # experts 0,1 carry more than half of all rows under Zipf(1.2)
     if key == "mixtral_ep4_cold":

@@ -143,14 +143,20 @@ def test_permute_is_deterministic():
 
 
 # ------------------------------------------------------------------ expert FFN
-def _ffn_gpu(x_perm_bits, offs, shard, wg, wu, wd, y_bf16=False):
+def _ffn_gpu(x_perm_bits, offs, shard, wg, wu, wd, y_bf16=False, gather=None):
+    """gather = (x_bits [T,H], row_src [cap], k): run moe_expert_ffn_gather on x instead of the permuted copy."""
     cap = x_perm_bits.shape[0]
     h_ws = torch.empty((cap, shard.inter_slice), dtype=torch.bfloat16, device="cuda")
     y = torch.full((cap, shard.hidden), float("nan"), dtype=torch.bfloat16 if y_bf16 else torch.float32,
                    device="cuda")
     ws = torch.empty(max(B.moe_ffn_workspace_bytes(cap, shard), 16), dtype=torch.uint8, device="cuda")
-    B.moe_expert_ffn(bf16_tensor(x_perm_bits), _dev(offs), cap, shard, bf16_tensor(wg), bf16_tensor(wu),
-                     bf16_tensor(wd), h_ws, y, ws, B.MOE_Y_PERM_BF16 if y_bf16 else 0)
+    if gather is not None:
+        x_bits, row_src, k = gather
+        B.moe_expert_ffn_gather(bf16_tensor(x_bits), _dev(row_src), k, _dev(offs), cap, shard, bf16_tensor(wg),
+                                bf16_tensor(wu), bf16_tensor(wd), h_ws, y, ws, B.MOE_Y_PERM_BF16 if y_bf16 else 0)
+    else:
+        B.moe_expert_ffn(bf16_tensor(x_perm_bits), _dev(offs), cap, shard, bf16_tensor(wg), bf16_tensor(wu),
+                         bf16_tensor(wd), h_ws, y, ws, B.MOE_Y_PERM_BF16 if y_bf16 else 0)
     torch.cuda.synchronize()
     return y.float().cpu().numpy().astype(np.float64)
 
@@ -220,7 +226,17 @@ def test_expert_ffn_random_shapes(seed):
     cap = max(cap, 1)
     xp = I.make_x(seed + 1, cap, H)
     shard = B.make_shard(E, n, 0, H, I_s, I_s)
-    y = _ffn_gpu(xp, offs, shard, wg, wu, wd)
+    gather = None
+    if seed % 2:   # the FFN reads rows of x through row_src instead of a permuted copy
+        k = int(rng.integers(1, 5))
+        T = max(1, (R + k - 1) // k + int(rng.integers(0, 5)))
+        x = I.make_x(seed + 2, T, H)
+        row_src = np.full(cap, -77777, dtype=np.int32)          # entries past R are never to be read
+        row_src[:R] = rng.permutation(T * k)[:R] if R <= T * k else rng.integers(0, T * k, R)
+        xp = np.zeros_like(xp)
+        xp[:R] = x[row_src[:R] // k]
+        gather = (x, row_src, k)
+    y = _ffn_gpu(xp, offs, shard, wg, wu, wd, gather=gather)
     assert np.all(np.isnan(y[R:])), "rows past R must not be written"
     if R:
         ref = O.expert_ffn(xp[:R], offs, wg, wu, wd)
@@ -320,7 +336,8 @@ def _check_integers(layer, li, T):
     assert np.array_equal(layer.expert_offsets.cpu().numpy(), offs)
     assert np.array_equal(layer.row_src[:R].cpu().numpy(), row_src)
     assert np.array_equal(layer.slot_row[:T * s.top_k].cpu().numpy(), slot_row)
-    assert np.array_equal(bf16_bits(layer.x_perm[:R]), x_perm)
+    if layer.x_perm is not None:
+        assert np.array_equal(bf16_bits(layer.x_perm[:R]), x_perm)
     return logits
 
 
