@@ -29,8 +29,8 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 # (FETCH_SIZE, WRITE_SIZE in KiB per dispatch; see profiles/<workload>_rocprofv3.txt), each scaled by
 # what the same counter reads for a plain 1 GiB device copy: FETCH_SIZE x 2.0, WRITE_SIZE x 1.0.
 MEASURED_TRAFFIC_BYTES = {
-    "mixtral_prefill": (1958653.6 * 2.0 + 232964.2) * 1024,
-    "mixtral_decode": (935096.4 * 2.0 + 898.4) * 1024,
+    "mixtral_prefill": (1958794.7 * 2.0 + 232966.6) * 1024,
+    "mixtral_decode": (937332.8 * 2.0 + 898.7) * 1024,
 }
 
 # name -> (inputs.WORKLOADS key, token count, description)
@@ -76,7 +76,9 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies, to scale FETCH_SIZE / WRITE_SIZE counters under rocprofv3")
     ap.add_argument("--permuted-copy", action="store_true",
-                    help="moe_permute writes x_perm and moe_expert_ffn reads it (default: the FFN gathers rows of x)")
+                    help="moe_permute writes x_perm and moe_expert_ffn reads it (default: the layer's own choice)")
+    ap.add_argument("--gather-rows", action="store_true",
+                    help="the FFN gathers its rows of x through row_src (default: the layer's own choice)")
     ap.add_argument("--no-overlap-shared", action="store_true",
                     help="run the shared expert after the routed experts instead of beside them on a second stream")
     ap.add_argument("--graph", choices=["auto", "on", "off"], default="auto",
@@ -111,7 +113,7 @@ def main():
     li = I.make_layer_inputs(shape, T, args.seed)
     gen_s = time.time() - t0
     layer = ExpertShardLayer.from_inputs(li, overlap_shared=not args.no_overlap_shared,
-                                         gather_in_ffn=not args.permuted_copy)
+                                         gather_in_ffn=False if args.permuted_copy else (True if args.gather_rows else None))
     x = bf16_tensor(li.x)
     logits = None if li.logits is None else torch.from_numpy(li.logits).cuda()
 

@@ -436,6 +436,18 @@ def test_layer_hybrid_ep_tp_shard():
     assert _rel(y, ref) < REL_L2 and np.abs(y - ref).max() < MAX_ABS
 
 
+@pytest.mark.parametrize("T", [24, 700])
+def test_layer_with_and_without_the_permuted_copy_gives_the_same_bits(T):
+    # the FFN either reads x_perm or gathers the same rows of x through row_src: same kernels, same
+    # operands, so the layer output must not differ in a single bit
+    li = I.make_layer_inputs(SMALL_QWEN, T, 0)
+    la, ya = _run_layer(li, gather_in_ffn=True)
+    lb, yb = _run_layer(li, gather_in_ffn=False)
+    assert la.x_perm is None and lb.x_perm is not None
+    assert np.array_equal(ya, yb)
+    _check_integers(lb, li, T)
+
+
 SMALL_ODD = I.MoEShape("small-odd", 256, 12, 4, 1408, False, inter_shared=704)
 
 
