@@ -69,16 +69,53 @@ __global__ __launch_bounds__(NW * 64, (MT == 1 ? 4 : 2)) void grouped_walk_kerne
   constexpr int TILES = NB * MT;
   __shared__ float red[2][NW][TILES][256];
 
-  const int e = blockIdx.y;
-  const int lo = expert_offsets[e], hi = expert_offsets[e + 1];
-  if (hi <= lo) return;  // inactive expert: its weights are never read
-
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l16 = lane & 15, kq = lane >> 4;
   const int total_strips = n_out / 16;
-  const int s_begin = blockIdx.x * strips_per_wg;
-  const int s_end = min(s_begin + strips_per_wg, total_strips);
+  // The workgroups of one K slice are shared out among the ACTIVE experts only (an inactive
+  // expert's weights are never read, and with few tokens many experts are inactive: 40 of 60 at
+  // 16 tokens): workgroup w of gridDim.x * gridDim.y works on the (w / share)-th active expert
+  // and on the (w % share)-th of `share` equal strip ranges.  Found with ballots over the experts,
+  // lane l looking at experts l, l + 64, ...; every wavefront computes the same values.
+  const int n_local = gridDim.y;
+  unsigned long long act[4] = {0, 0, 0, 0};
+  int n_act = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (j * 64 < n_local) {
+      const int ee = j * 64 + lane;
+      const bool on = ee < n_local && expert_offsets[ee + 1] > expert_offsets[ee];
+      act[j] = __ballot(on);
+      n_act += __popcll(act[j]);
+    }
+  }
+  if (n_act == 0) return;
+  const int w = blockIdx.y * gridDim.x + blockIdx.x;
+  const int share = (int)(gridDim.x * gridDim.y) / n_act;  // >= gridDim.x
+  const int a = w / share, part = w - a * share;
+  if (a >= n_act) return;
+  int e = 0, skip = a;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (j * 64 < n_local) {
+      const int cnt = __popcll(act[j]);
+      if (skip >= 0 && skip < cnt) {  // the skip-th set bit of this mask
+        const unsigned long long below = act[j] & ((1ull << lane) - 1ull);
+        const unsigned long long hit = __ballot(((act[j] >> lane) & 1ull) && __popcll(below) == skip);
+        e = j * 64 + __ffsll((long long)hit) - 1;
+        skip = -1;
+      } else if (skip >= 0) {
+        skip -= cnt;
+      }
+    }
+  }
+  e = __builtin_amdgcn_readfirstlane(e);
+  const int lo = expert_offsets[e], hi = expert_offsets[e + 1];
+  const int per_part = (total_strips + share - 1) / share;
+  (void)strips_per_wg;
+  const int s_begin = part * per_part;
+  const int s_end = min(s_begin + per_part, total_strips);
   if (s_begin >= s_end) return;
   const int n_strips = s_end - s_begin;
   const int kbase = (blockIdx.z * NW + wave) * (STEPS * 32) + kq * 8;
