@@ -228,7 +228,7 @@ hipError_t launch_route_topk(const void* x, const float* w_router, float* logits
   const uint16_t* xs = static_cast<const uint16_t*>(x);
   if (!(flags & MOE_LOGITS_GIVEN) && H % 32 == 0) {
     const int nt = (E + 15) / 16;
-    if (nt < 2 || T > 128) {  // logits by MFMA and the selection from the logits tile, in one kernel
+    if (nt < 2 || T > 1024) {  // logits by MFMA and the selection from the logits tile, in one kernel
       if (nt <= 1) launch_logits<1, 16, 4>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
       else if (nt <= 2) launch_logits<2, 16, 4>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
       else if (nt <= 4) launch_logits<4, 16, 2>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
@@ -236,7 +236,8 @@ hipError_t launch_route_topk(const void* x, const float* w_router, float* logits
       else launch_logits<16, 4, 1>(xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w, stream);
       return hipGetLastError();
     }
-    // few tokens, many experts: one workgroup per (16 tokens, 16 experts), then select from the logits
+    // up to 1024 tokens and more than 16 experts: one workgroup per (16 tokens, 16 experts), then select
+    // from the logits (measured at 60 experts: 11 against 21 us at 256 and 1024 tokens, 31 against 24 us at 4096)
     hipLaunchKernelGGL((router_logits_kernel<1, 16, 4, false>), dim3((T + kLogitTok - 1) / kLogitTok, nt),
                        dim3(16 * 64), 0, stream, xs, w_router, logits, T, H, E, k, flags, topk_idx, topk_w);
     if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
