@@ -136,6 +136,24 @@ def main():
         graph, _ = layer.capture(x, logits)
         ms_per_step, mode = timed(graph.replay), "hip-graph"
 
+    # per-step spread (median and minimum over the same number of steps, one event pair per step) and the
+    # device copy rate of this GPU, for reading the HBM fractions against something measured
+    run_step = graph.replay if mode == "hip-graph" else step
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    for a, b in evs:
+        a.record()
+        run_step()
+        b.record()
+    torch.cuda.synchronize()
+    per_step = sorted(a.elapsed_time(b) for a, b in evs)
+    step_median_ms, step_min_ms = per_step[len(per_step) // 2], per_step[0]
+    cbuf = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    cdst = torch.empty_like(cbuf)
+    copy_ms = time_events(lambda: cdst.copy_(cbuf), 10, torch)
+    copy_gbs = 2.0 * cbuf.numel() / (copy_ms * 1e-3) / 1e9   # bytes read + bytes written
+    del cbuf, cdst
+
     counts = np.diff(layer.expert_offsets.cpu().numpy())
     flops, min_bytes, R, active = algorithmic_work(shape, T, counts)
     tflops = flops / (ms_per_step * 1e-3) / 1e12
@@ -229,7 +247,8 @@ def main():
                    "n_local_experts": shape.n_local_experts, "expert_offset": shape.expert_offset, "seed": args.seed},
         "pct_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS, "min_bytes_gbs": gbs,
         "pct_hbm_peak": 100.0 * gbs / PEAK_HBM_GBS, "flops_per_layer": flops, "min_bytes_per_layer": min_bytes,
-        "launch_mode": mode, "eager_ms_per_step": eager_ms, "breakdown_ms": br, "input_gen_s": gen_s, "roofline": roofline, "cpu_baseline": cpu,
+        "launch_mode": mode, "eager_ms_per_step": eager_ms, "step_ms_median": step_median_ms,
+        "step_ms_min": step_min_ms, "device_copy_gbs": copy_gbs, "breakdown_ms": br, "input_gen_s": gen_s, "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
 

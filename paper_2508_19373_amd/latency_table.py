@@ -34,6 +34,20 @@ def legal_shards(shape, max_devices=8):
     return out
 
 
+def weight_sets(layer, total_bytes=1 << 30):
+    """The layer's weights plus as many device copies as it takes to exceed `total_bytes` in all."""
+    def nbytes(ws):
+        return sum(t.numel() * t.element_size() for t in ws[:3]) + \
+            (sum(t.numel() * t.element_size() for t in ws[3]) if ws[3] is not None else 0)
+    first = (layer.w_gate, layer.w_up, layer.w_down, layer.shared)
+    sets = [first]
+    one = max(nbytes(first), 1)
+    while len(sets) * one < total_bytes and len(sets) < 16:
+        sets.append((first[0].clone(), first[1].clone(), first[2].clone(),
+                     None if first[3] is None else [t.clone() for t in first[3]]))
+    return sets
+
+
 def measure(shape, tokens, seed=0, steps=60, warmup=30):
     import numpy as np
     import torch
@@ -60,10 +74,37 @@ def measure(shape, tokens, seed=0, steps=60, warmup=30):
             torch.cuda.synchronize()
             return (time.perf_counter() - t0) * 1e6 / steps
 
-        us, mode = timed(lambda: layer.forward(x, logits)), "eager"
+        # a shard whose weights fit the last-level cache (256 MB) would be served from it when the same
+        # buffers are replayed; in a model every layer has its own weights.  Rotate over copies
+        # that together exceed 1 GB.
+        sets = weight_sets(layer)
+
+        def use(ws):
+            layer.w_gate, layer.w_up, layer.w_down, layer.shared = ws
+
+        def rotating(fns):
+            state = {"i": 0}
+
+            def run():
+                fns[state["i"] % len(fns)]()
+                state["i"] += 1
+            return run
+
+        def eager_on(ws):
+            def run():
+                use(ws)
+                layer.forward(x, logits)
+            return run
+
+        us, mode = timed(rotating([eager_on(ws) for ws in sets])), "eager"
         if us < 1000.0:
-            graph, _ = layer.capture(x, logits)
-            us, mode = timed(graph.replay), "hip-graph"
+            graphs = []
+            for ws in sets:
+                use(ws)
+                graphs.append(layer.capture(x, logits)[0])
+            us, mode = timed(rotating([g.replay for g in graphs])), "hip-graph"
+            del graphs
+        use(sets[0])
         counts = np.diff(layer.expert_offsets.cpu().numpy())
         flops, min_bytes, R, active = algorithmic_work(shape, T, counts)
         rows.append(dict(model=shape.name, hidden=shape.hidden, n_experts=shape.n_experts, top_k=shape.top_k,
