@@ -194,7 +194,7 @@ def main():
     g1_flops = 4.0 * R * H * I_s
     g1_bytes = 2.0 * active * H * I_s * 2 + R * H * 2 + R * I_s * 2
     intensity = g1_flops / g1_bytes
-    decode = (T * k) // shape.n_local_experts <= 20
+    decode = B.moe_debug_ffn_plan(T * k, layer.ffn_shard)[0]   # GEMM1 takes the weight-streaming kernel
     kname = ("moe::gw::grouped_walk_kernel<..., GATEUP> (GEMM1 + SwiGLU, weight streaming)" if decode
              else "moe::gg::grouped_gemm_dlds_kernel<256, GATEUP> (GEMM1 + SwiGLU)")
     if intensity > PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
@@ -209,6 +209,10 @@ def main():
                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
                     "ms": g1_ms, "bytes_per_launch": g1_bytes}
+
+    if 2.0 * active * H * I_s * 2 < 256e6:
+        roofline["note"] = ("GEMM1's weights (%.0f MB) fit the 256 MB last-level cache and are replayed from one "
+                            "buffer here: not an HBM measurement" % (2.0 * active * H * I_s * 2 / 1e6))
 
     # ---- CPU baseline: the oracle as it stands on a bounded token sample
     cpu = None
