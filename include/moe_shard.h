@@ -49,7 +49,8 @@ enum {
   MOE_Y_PERM_BF16 = 1u << 2,  /* moe_expert_ffn / moe_combine: y_perm, y_shared are bf16 (default fp32) */
   MOE_OUT_F32 = 1u << 3,      /* moe_combine: y_out is fp32 (default bf16)                    */
   MOE_FFN_SKIP_GATEUP = 1u << 4, /* moe_expert_ffn: do not run GEMM1; h_workspace is an input  */
-  MOE_FFN_SKIP_DOWN = 1u << 5    /* moe_expert_ffn: stop after GEMM1; y_perm is not written    */
+  MOE_FFN_SKIP_DOWN = 1u << 5,   /* moe_expert_ffn: stop after GEMM1; y_perm is not written    */
+  MOE_FFN_TILED = 1u << 6        /* moe_expert_ffn: tiled kernels whatever the cost estimate says */
 };
 
 /* limits of this implementation */
@@ -128,6 +129,13 @@ int moe_permute(const void* x_bf16, const int32_t* topk_idx, int32_t T, int32_t 
  * x_perm = x.  Requires H % 64 == 0, I_s % 64 == 0, cap_rows >= 0.
  * MOE_FFN_SKIP_GATEUP / MOE_FFN_SKIP_DOWN run one of the two GEMMs alone (operator-level
  * benchmarking, as the paper's latency model is fitted on measured operator latencies).
+ * MOE_FFN_TILED: each GEMM normally picks, from a cost estimate, between a weight-streaming kernel
+ * (few rows per expert) and the tiled MFMA kernel; with this flag both run tiled.  It is meant
+ * for a call that overlaps a tiled call on another stream (routed experts beside a shared
+ * expert with a few dozen rows or more): the streaming kernel's workgroups stay resident on every compute unit
+ * for the whole launch, and a tiled workgroup, which needs a compute unit's whole LDS, cannot
+ * start beside them, so the two calls would run one after the other.  Same results to rounding
+ * order; the workspace size covers either choice.
  */
 int moe_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int32_t cap_rows,
                    const moe_shard_t* shard, const void* w_gate, const void* w_up,
@@ -168,8 +176,9 @@ size_t moe_workspace_bytes(int32_t T, int32_t k, const moe_shard_t* shard);
 
 /* Bytes of scratch moe_expert_ffn needs for (cap_rows, shard); 0 if none (or invalid arguments).
  * It holds the fp32 partial sums of whatever the down projection cuts along K for a routing: a
- * few slices of cap_rows x H floats in the decoding regime, at most 65536 / ceil(H / 256) rows of
- * H floats in the prefill regime (whatever the capacity). */
+ * few slices of cap_rows x H floats in the decoding regime (and never less than the tiled kernels
+ * would need, so that MOE_FFN_TILED may be set), at most 65536 / ceil(H / 256) rows of H floats in
+ * the prefill regime (whatever the capacity). */
 size_t moe_ffn_workspace_bytes(int32_t cap_rows, const moe_shard_t* shard);
 
 /* Static, NUL-terminated description of a status code. */

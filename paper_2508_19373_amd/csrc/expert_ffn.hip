@@ -79,15 +79,14 @@ template <int MT, bool GATEUP>
 bool launch_walk(const gw::WalkPlan& plan, const uint16_t* A, const int32_t* expert_offsets, int n_local,
                  const uint16_t* Wa, const uint16_t* Wb, int n_out, int K, void* C, int cap_rows, RowMap rows,
                  hipStream_t stream) {
-  const int total_strips = n_out / 16;
-  int chunks = (MT == 1 && plan.nw < 16 ? kWalkSlots : kWalkSlots / 2) / (n_local * plan.slices);
-  chunks = chunks < 1 ? 1 : (chunks > total_strips ? total_strips : chunks);
-  const int spw = (total_strips + chunks - 1) / chunks;
-  const dim3 grid((total_strips + spw - 1) / spw, n_local, plan.slices);
+  // as many workgroups as are resident at once; the kernel cuts its work list into that many ranges
+  int n_wg = (MT == 1 && plan.nw < 16 ? kWalkSlots : kWalkSlots / 2) / plan.slices;
+  n_wg = n_wg < 1 ? 1 : n_wg;
+  const dim3 grid(n_wg, 1, plan.slices);
 #define MOE_WALK(NW, ST)                                                                                        \
   if (plan.nw == NW && plan.steps == ST) {                                                                      \
     hipLaunchKernelGGL((gw::grouped_walk_kernel<NW, ST, MT, GATEUP>), grid, dim3(NW * 64), 0, stream, A,        \
-                       expert_offsets, Wa, Wb, n_out, K, C, spw, cap_rows, rows);                               \
+                       expert_offsets, Wa, Wb, n_out, K, C, n_local, cap_rows, rows);                               \
     return true;                                                                                                \
   }
   if constexpr (MT == 1) {
@@ -208,14 +207,13 @@ inline bool prefer_walk(int cap_rows, int est_rows, int n_local, int n_out, int 
 
 size_t ffn_workspace_bytes(int cap_rows, int est_rows, int n_local, int H, int I_s) {
   if (cap_rows == 0) return 0;
-  int slices;
-  if (prefer_walk(cap_rows, est_rows, n_local, H, I_s, false)) {
-    const gw::WalkPlan p2 = gw::plan_for(I_s, decode_mt(cap_rows, est_rows, n_local));
-    slices = p2.nw == 0 ? 1 : p2.slices;
-  } else {
-    return (size_t)gg::slice_plan(cap_rows, (H + 255) / 256, I_s).scratch_rows * H * sizeof(float);
-  }
-  return slices > 1 ? (size_t)slices * cap_rows * H * sizeof(float) : 0;
+  // what the tiled kernels need is always covered: MOE_FFN_TILED may overrule the estimate
+  const size_t tiled = (size_t)gg::slice_plan(cap_rows, (H + 255) / 256, I_s).scratch_rows * H * sizeof(float);
+  if (!prefer_walk(cap_rows, est_rows, n_local, H, I_s, false)) return tiled;
+  const gw::WalkPlan p2 = gw::plan_for(I_s, decode_mt(cap_rows, est_rows, n_local));
+  const int slices = p2.nw == 0 ? 1 : p2.slices;
+  const size_t walk = slices > 1 ? (size_t)slices * cap_rows * H * sizeof(float) : 0;
+  return walk > tiled ? walk : tiled;
 }
 
 void ffn_plan(int cap_rows, int est_rows, int n_local, int H, int I_s, int32_t out[4]) {
@@ -251,8 +249,9 @@ hipError_t launch_expert_ffn(const void* x_perm, RowMap rows, const int32_t* exp
     return launch_pair_decode<2>(x_perm, rows, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,
                                  y_perm, workspace, f, stream);
   };
-  const bool walk1 = prefer_walk(cap_rows, est_rows, n_local, I_s, H, true),
-             walk2 = prefer_walk(cap_rows, est_rows, n_local, H, I_s, false);
+  const bool tiled_only = (flags & MOE_FFN_TILED) != 0;
+  const bool walk1 = !tiled_only && prefer_walk(cap_rows, est_rows, n_local, I_s, H, true),
+             walk2 = !tiled_only && prefer_walk(cap_rows, est_rows, n_local, H, I_s, false);
   if (walk1 == walk2 || (flags & (MOE_FFN_SKIP_GATEUP | MOE_FFN_SKIP_DOWN)))
     return run((flags & MOE_FFN_SKIP_GATEUP) ? walk2 : walk1, flags);
   const hipError_t err = run(walk1, flags | MOE_FFN_SKIP_DOWN);

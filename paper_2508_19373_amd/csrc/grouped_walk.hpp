@@ -19,6 +19,7 @@
 #include <type_traits>
 
 #include "moe_internal.hpp"
+#include "unit_list_wave.hpp"
 
 namespace moe {
 namespace gw {
@@ -55,7 +56,7 @@ constexpr int ring_size(int n) {
 template <int NW, int STEPS, int MT, bool GATEUP>
 __global__ __launch_bounds__(NW * 64, (MT == 1 ? 4 : 2)) void grouped_walk_kernel(
     const uint16_t* __restrict__ A, const int32_t* __restrict__ expert_offsets, const uint16_t* __restrict__ Wa,
-    const uint16_t* __restrict__ Wb, int n_out, int K, void* __restrict__ Cv, int strips_per_wg, int cap_rows,
+    const uint16_t* __restrict__ Wb, int n_out, int K, void* __restrict__ Cv, int n_local, int cap_rows,
     const RowMap rows) {
   constexpr int NB = GATEUP ? 2 : 1;
   constexpr int ITEMS = NB * STEPS;  // weight loads (1 KB each) per strip per wave
@@ -73,60 +74,72 @@ __global__ __launch_bounds__(NW * 64, (MT == 1 ? 4 : 2)) void grouped_walk_kerne
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l16 = lane & 15, kq = lane >> 4;
   const int total_strips = n_out / 16;
-  // The workgroups of one K slice are shared out among the ACTIVE experts only (an inactive
-  // expert's weights are never read, and with few tokens many experts are inactive: 40 of 60 at
-  // 16 tokens): workgroup w of gridDim.x * gridDim.y works on the (w / share)-th active expert
-  // and on the (w % share)-th of `share` equal strip ranges.  Found with ballots over the experts,
-  // lane l looking at experts l, l + 64, ...; every wavefront computes the same values.
-  const int n_local = gridDim.y;
-  unsigned long long act[4] = {0, 0, 0, 0};
-  int n_act = 0;
+  // The work of one K slice is the list of (expert, row pass, strip) in that order: an expert with
+  // rows has ceil(rows / (16 MT)) passes, each walking all of its strips; one without rows has
+  // none, so its weights are never read (with few tokens many experts are inactive: 40 of 60 at
+  // 16 tokens).  The workgroups cut this list into equal contiguous ranges, so an expert that
+  // needs a second pass (a skewed routing puts 20 rows on one expert when the average is 6) costs
+  // its share of extra strips to everybody instead of doubling the run time of its own
+  // workgroups.  Such a range may end one (expert, pass) and begin the next.  Lane l looks at experts
+  // l, l + 64, ...; every wavefront computes the same values.
+  const int chunks = (n_local + 63) >> 6;
+  // The per-lane tables live only inside this function: a second range reads them again rather
+  // than holding 16 registers through the strip loop.  Returns the number of (expert, pass) units;
+  // with u >= 0 also that unit's expert, first row and the expert's end row.
+  auto find_unit = [&](int u, int& e, int& m0, int& hi, int& g, int& g_end) {
+    int pas[gg::kLaneChunks], pre[gg::kLaneChunks], lo_[gg::kLaneChunks], hi_[gg::kLaneChunks];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    if (j * 64 < n_local) {
+    for (int j = 0; j < gg::kLaneChunks; ++j) {
       const int ee = j * 64 + lane;
-      const bool on = ee < n_local && expert_offsets[ee + 1] > expert_offsets[ee];
-      act[j] = __ballot(on);
-      n_act += __popcll(act[j]);
+      const bool ok = j < chunks && ee < n_local;
+      lo_[j] = ok ? expert_offsets[ee] : 0;
+      hi_[j] = ok ? expert_offsets[ee + 1] : 0;
+      pas[j] = (hi_[j] - lo_[j] + 16 * MT - 1) / (16 * MT);
     }
-  }
-  if (n_act == 0) return;
-  const int w = blockIdx.y * gridDim.x + blockIdx.x;
-  const int share = (int)(gridDim.x * gridDim.y) / n_act;  // >= gridDim.x
-  const int a = w / share, part = w - a * share;
-  if (a >= n_act) return;
-  int e = 0, skip = a;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    if (j * 64 < n_local) {
-      const int cnt = __popcll(act[j]);
-      if (skip >= 0 && skip < cnt) {  // the skip-th set bit of this mask
-        const unsigned long long below = act[j] & ((1ull << lane) - 1ull);
-        const unsigned long long hit = __ballot(((act[j] >> lane) & 1ull) && __popcll(below) == skip);
-        e = j * 64 + __ffsll((long long)hit) - 1;
-        skip = -1;
-      } else if (skip >= 0) {
-        skip -= cnt;
+    const int units = gg::wave_prefix(pas, chunks, pre);
+    if (u < 0) {  // first call: this workgroup's range [g, g_end) of the list, then its first unit
+      const int n_wg = gridDim.x, total = units * total_strips;
+      const int per_wg = (total + n_wg - 1) / n_wg;
+      g = blockIdx.x * per_wg;
+      g_end = min(g + per_wg, total);
+      // A range that crosses into the next (expert, pass) reloads its activations and refills
+      // the weight ring (about half a strip's time, with nothing else on the compute unit to
+      // hide it), so when giving every (expert, pass) the same whole number of workgroups comes
+      // out no longer than the equal cut, that is used instead and no range crosses.
+      if (units > 0 && units <= n_wg) {
+        const int share = n_wg / units, per_part = (total_strips + share - 1) / share;
+        if (per_part <= per_wg) {
+          const int uu = (int)blockIdx.x / share, part = (int)blockIdx.x - uu * share;
+          g = uu * total_strips + part * per_part;
+          g_end = uu < units ? min(g + per_part, (uu + 1) * total_strips) : g;
+        }
       }
+      if (g >= g_end) return;
+      u = g / total_strips;
     }
-  }
-  e = __builtin_amdgcn_readfirstlane(e);
-  const int lo = expert_offsets[e], hi = expert_offsets[e + 1];
-  const int per_part = (total_strips + share - 1) / share;
-  (void)strips_per_wg;
-  const int s_begin = part * per_part;
-  const int s_end = min(s_begin + per_part, total_strips);
-  if (s_begin >= s_end) return;
-  const int n_strips = s_end - s_begin;
+    const gg::WaveHit h = gg::wave_find(pre, pas, chunks, u);
+    e = __builtin_amdgcn_readfirstlane(h.lane + 64 * h.j);
+    hi = __builtin_amdgcn_readfirstlane(gg::wave_pick(hi_, h));
+    m0 = __builtin_amdgcn_readfirstlane(gg::wave_pick(lo_, h) + (u - gg::wave_pick(pre, h)) * 16 * MT);
+  };
+  int e = 0, m0 = 0, hi = 0, g = 0, g_end = 0;
+  find_unit(-1, e, m0, hi, g, g_end);
   const int kbase = (blockIdx.z * NW + wave) * (STEPS * 32) + kq * 8;
-
-  const size_t eoff = (size_t)e * n_out * K;
-  const uint16_t* w_lane[NB];
-  w_lane[0] = Wa + eoff + (size_t)(s_begin * 16 + l16) * K + kbase;
-  if constexpr (GATEUP) w_lane[1] = Wb + eoff + (size_t)(s_begin * 16 + l16) * K + kbase;
   const size_t strip_stride = (size_t)16 * K;
 
-  for (int m0 = lo; m0 < hi; m0 += 16 * MT) {
+  bool first = true;
+  while (g < g_end) {
+    const int u = g / total_strips;
+    const int s_begin = g - u * total_strips;
+    const int n_strips = min(total_strips - s_begin, g_end - g);
+    if (!first) find_unit(u, e, m0, hi, g, g_end);
+    first = false;
+    g += n_strips;
+    const size_t eoff = (size_t)e * n_out * K;
+    const uint16_t* w_lane[NB];
+    w_lane[0] = Wa + eoff + (size_t)(s_begin * 16 + l16) * K + kbase;
+    if constexpr (GATEUP) w_lane[1] = Wb + eoff + (size_t)(s_begin * 16 + l16) * K + kbase;
+    {
     const int m_hi = min(m0 + 16 * MT, hi);
     // ---- activations: loaded once, kept for every strip
     bf16x8 a[STEPS][MT];
@@ -196,7 +209,8 @@ __global__ __launch_bounds__(NW * 64, (MT == 1 ? 4 : 2)) void grouped_walk_kerne
       }
       // no second barrier: buffer `buf` is written again two strips later, after the next barrier
     }
-    __syncthreads();  // before the next row pass reuses the LDS buffers
+    }
+    __syncthreads();  // before the next range reuses the LDS buffers
   }
 }
 

@@ -64,7 +64,7 @@ def test_header_constants_match_binding():
         m = re.search(name + r"\s*=\s*(-?\d+)", src)
         assert int(m.group(1)) == getattr(B, name)
     for name in ("MOE_RENORM_TOPK", "MOE_LOGITS_GIVEN", "MOE_Y_PERM_BF16", "MOE_OUT_F32", "MOE_FFN_SKIP_GATEUP",
-                 "MOE_FFN_SKIP_DOWN"):
+                 "MOE_FFN_SKIP_DOWN", "MOE_FFN_TILED"):
         m = re.search(name + r"\s*=\s*1u\s*<<\s*(\d+)", src)
         assert 1 << int(m.group(1)) == getattr(B, name)
     assert ctypes.sizeof(B.MoeShard) == 24
@@ -144,7 +144,9 @@ def test_expert_ffn_validation(lib):
     # partial sums of tiles cut along K (65536 / 16 column blocks rows, whatever the capacity)
     mix = _shard(hidden=4096, inter_full=14336, inter_slice=14336)
     need = B.moe_ffn_workspace_bytes(32, mix)
-    assert need == 2 * 32 * 4096 * 4   # 16 wavefronts x 14 k-steps x 2 K slices
+    # streaming kernel: 16 wavefronts x 14 k-steps x 2 K slices of 32 rows; the tiled kernels, which
+    # MOE_FFN_TILED may ask for, up to 15 further slices of the 32 rows: the larger of the two
+    assert need == max(2 * 32 * 4096 * 4, 15 * 32 * 4096 * 4)
     assert B.moe_ffn_workspace_bytes(8192, mix) == 4096 * 4096 * 4
     assert B.moe_ffn_workspace_bytes(8192, _shard(hidden=4096, inter_full=512, inter_slice=512)) == 0   # K too short to cut
     # a single expert with a few hundred rows: the tiled down projection is cut along K

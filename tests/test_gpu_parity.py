@@ -143,7 +143,7 @@ def test_permute_is_deterministic():
 
 
 # ------------------------------------------------------------------ expert FFN
-def _ffn_gpu(x_perm_bits, offs, shard, wg, wu, wd, y_bf16=False, gather=None):
+def _ffn_gpu(x_perm_bits, offs, shard, wg, wu, wd, y_bf16=False, gather=None, flags=0):
     """gather = (x_bits [T,H], row_src [cap], k): run moe_expert_ffn_gather on x instead of the permuted copy."""
     cap = x_perm_bits.shape[0]
     h_ws = torch.empty((cap, shard.inter_slice), dtype=torch.bfloat16, device="cuda")
@@ -153,10 +153,11 @@ def _ffn_gpu(x_perm_bits, offs, shard, wg, wu, wd, y_bf16=False, gather=None):
     if gather is not None:
         x_bits, row_src, k = gather
         B.moe_expert_ffn_gather(bf16_tensor(x_bits), _dev(row_src), k, _dev(offs), cap, shard, bf16_tensor(wg),
-                                bf16_tensor(wu), bf16_tensor(wd), h_ws, y, ws, B.MOE_Y_PERM_BF16 if y_bf16 else 0)
+                                bf16_tensor(wu), bf16_tensor(wd), h_ws, y, ws,
+                                flags | (B.MOE_Y_PERM_BF16 if y_bf16 else 0))
     else:
         B.moe_expert_ffn(bf16_tensor(x_perm_bits), _dev(offs), cap, shard, bf16_tensor(wg), bf16_tensor(wu),
-                         bf16_tensor(wd), h_ws, y, ws, B.MOE_Y_PERM_BF16 if y_bf16 else 0)
+                         bf16_tensor(wd), h_ws, y, ws, flags | (B.MOE_Y_PERM_BF16 if y_bf16 else 0))
     torch.cuda.synchronize()
     return y.float().cpu().numpy().astype(np.float64)
 
@@ -197,6 +198,47 @@ def test_expert_ffn_against_oracle(H, I_s, counts):
     assert np.abs(y[:R] - ref).max() < MAX_ABS
     yb = _ffn_gpu(xp, offs, shard, wg, wu, wd, y_bf16=True)
     assert _rel(yb[:R], ref) < REL_L2
+
+
+def test_expert_ffn_streaming_kernel_with_experts_that_need_several_row_passes():
+    """24 small experts, three of them with 17 to 33 rows: 26 (expert, pass) units over 256
+    workgroups do not divide evenly, so the ranges of the streaming kernel cross from one unit into
+    the next."""
+    H, I_s = 2048, 1408
+    counts = [3, 1, 0, 17, 5, 2, 8, 33, 1, 4, 0, 6, 2, 9, 20, 1, 3, 7, 2, 5, 1, 4, 6, 2]
+    n = len(counts)
+    wg, wu, wd = I.make_expert_weights(3, I.MoEShape("f", H, n, 1, I_s, True))
+    offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    R = int(offs[-1])
+    cap = R + 7
+    shard = B.make_shard(n, n, 0, H, I_s, I_s)
+    assert B.moe_debug_ffn_plan(cap, shard)[:3] == (True, True, 1)   # streaming kernels, 16 rows per pass
+    xp = I.make_x(4, cap, H)
+    ref = O.expert_ffn(xp[:R], offs, wg, wu, wd)
+    y = _ffn_gpu(xp, offs, shard, wg, wu, wd)
+    assert np.all(np.isnan(y[R:]))
+    assert _rel(y[:R], ref) < REL_L2 and np.abs(y[:R] - ref).max() < MAX_ABS
+    # the same call on the tiled kernels
+    yt = _ffn_gpu(xp, offs, shard, wg, wu, wd, flags=B.MOE_FFN_TILED)
+    assert np.all(np.isnan(yt[R:]))
+    assert _rel(yt[:R], ref) < REL_L2 and np.abs(yt[:R] - ref).max() < MAX_ABS
+
+
+@pytest.mark.parametrize("H,I_s,counts", [(4096, 3584, [2, 0, 5, 1]), (2048, 5632, [12]), (512, 1024, [16, 2, 0, 9])])
+def test_expert_ffn_tiled_flag_on_decode_sized_calls(H, I_s, counts):
+    n = len(counts)
+    wg, wu, wd = I.make_expert_weights(0, I.MoEShape("f", H, n, 1, I_s, True))
+    offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    R = int(offs[-1])
+    cap = R + 7
+    xp = I.make_x(1, cap, H)
+    shard = B.make_shard(n, n, 0, H, I_s, I_s)
+    assert any(B.moe_debug_ffn_plan(cap, shard)[:2])     # left alone, this call streams
+    ref = O.expert_ffn(xp[:R], offs, wg, wu, wd)
+    for y_bf16 in (False, True):
+        y = _ffn_gpu(xp, offs, shard, wg, wu, wd, y_bf16=y_bf16, flags=B.MOE_FFN_TILED)
+        assert np.all(np.isnan(y[R:]))
+        assert _rel(y[:R], ref) < REL_L2
 
 
 @pytest.mark.parametrize("seed", range(24))
@@ -405,7 +447,7 @@ def test_layer_ep_shards_and_union_invariant(ep):
 
 
 @pytest.mark.parametrize("overlap", [True, False])
-@pytest.mark.parametrize("T", [32, 500])
+@pytest.mark.parametrize("T", [32, 96, 500])
 def test_layer_qwen_like_with_shared_expert(T, overlap):
     li = I.make_layer_inputs(SMALL_QWEN, T, 0)
     layer, y = _run_layer(li, overlap_shared=overlap)
