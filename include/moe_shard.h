@@ -50,7 +50,8 @@ enum {
   MOE_OUT_F32 = 1u << 3,      /* moe_combine: y_out is fp32 (default bf16)                    */
   MOE_FFN_SKIP_GATEUP = 1u << 4, /* moe_expert_ffn: do not run GEMM1; h_workspace is an input  */
   MOE_FFN_SKIP_DOWN = 1u << 5,   /* moe_expert_ffn: stop after GEMM1; y_perm is not written    */
-  MOE_FFN_TILED = 1u << 6        /* moe_expert_ffn: tiled kernels whatever the cost estimate says */
+  MOE_FFN_TILED = 1u << 6,       /* moe_expert_ffn: tiled kernels whatever the cost estimate says */
+  MOE_FFN_LEAVE_ROOM = 1u << 7   /* moe_expert_ffn: streaming kernels leave 1/16 of the compute units free */
 };
 
 /* limits of this implementation */
@@ -136,6 +137,9 @@ int moe_permute(const void* x_bf16, const int32_t* topk_idx, int32_t T, int32_t 
  * for the whole launch, and a tiled workgroup, which needs a compute unit's whole LDS, cannot
  * start beside them, so the two calls would run one after the other.  Same results to rounding
  * order; the workspace size covers either choice.
+ * MOE_FFN_LEAVE_ROOM is the milder form for the same situation when the call has too few tiles to
+ * stream well on the tiled kernels: a streaming kernel then launches 15 of every 16 workgroups it
+ * would, so 16 compute units stay free for the other stream.  Same results, bit for bit.
  */
 int moe_expert_ffn(const void* x_perm, const int32_t* expert_offsets, int32_t cap_rows,
                    const moe_shard_t* shard, const void* w_gate, const void* w_up,

@@ -23,6 +23,7 @@ MOE_OUT_F32 = 1 << 3
 MOE_FFN_SKIP_GATEUP = 1 << 4
 MOE_FFN_SKIP_DOWN = 1 << 5
 MOE_FFN_TILED = 1 << 6
+MOE_FFN_LEAVE_ROOM = 1 << 7
 MOE_MAX_EXPERTS = 256
 MOE_MAX_TOPK = 16
 

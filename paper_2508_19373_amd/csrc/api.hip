@@ -81,7 +81,8 @@ static int expert_ffn_common(const void* x, moe::RowMap rows, const int32_t* exp
                              void* stream) {
   const int st = shard_status(shard);
   if (st != MOE_OK) return st;
-  if (cap_rows < 0 || (flags & ~(uint32_t)(MOE_Y_PERM_BF16 | MOE_FFN_SKIP_GATEUP | MOE_FFN_SKIP_DOWN | MOE_FFN_TILED)))
+  if (cap_rows < 0 || (flags & ~(uint32_t)(MOE_Y_PERM_BF16 | MOE_FFN_SKIP_GATEUP | MOE_FFN_SKIP_DOWN | MOE_FFN_TILED |
+                                       MOE_FFN_LEAVE_ROOM)))
     return MOE_ERR_INVALID_ARG;
   if (x == nullptr || expert_offsets == nullptr || w_gate == nullptr || w_up == nullptr ||
       w_down == nullptr || h_workspace == nullptr || y_perm == nullptr)

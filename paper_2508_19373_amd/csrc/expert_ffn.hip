@@ -78,9 +78,10 @@ constexpr int kWalkSlots = 512;  // 8-wavefront workgroups resident at once with
 template <int MT, bool GATEUP>
 bool launch_walk(const gw::WalkPlan& plan, const uint16_t* A, const int32_t* expert_offsets, int n_local,
                  const uint16_t* Wa, const uint16_t* Wb, int n_out, int K, void* C, int cap_rows, RowMap rows,
-                 hipStream_t stream) {
+                 bool leave_room, hipStream_t stream) {
   // as many workgroups as are resident at once; the kernel cuts its work list into that many ranges
   int n_wg = (MT == 1 && plan.nw < 16 ? kWalkSlots : kWalkSlots / 2) / plan.slices;
+  if (leave_room) n_wg = n_wg * 15 / 16;  // 16 compute units stay free for a tiled call on another stream
   n_wg = n_wg < 1 ? 1 : n_wg;
   const dim3 grid(n_wg, 1, plan.slices);
 #define MOE_WALK(NW, ST)                                                                                        \
@@ -125,7 +126,8 @@ hipError_t launch_pair_decode(const void* x_perm, RowMap rows, const int32_t* ex
     bool done = false;
     if (p1.nw != 0 && p1.slices == 1 && I_s % 16 == 0)
       done = launch_walk<MT, true>(p1, xp, expert_offsets, n_local, static_cast<const uint16_t*>(w_gate),
-                                   static_cast<const uint16_t*>(w_up), I_s, H, hw, cap_rows, rows, stream);
+                                   static_cast<const uint16_t*>(w_up), I_s, H, hw, cap_rows, rows,
+                                   (flags & MOE_FFN_LEAVE_ROOM) != 0, stream);
     if (!done) {
       const dim3 grid((I_s + gs::kStripN - 1) / gs::kStripN, n_local);
       hipLaunchKernelGGL((gs::grouped_stream_kernel<MT, true, uint16_t>), grid, dim3(gs::kWaves * 64), 0, stream, xp,
@@ -140,7 +142,8 @@ hipError_t launch_pair_decode(const void* x_perm, RowMap rows, const int32_t* ex
   if (!y_bf16 && p2.nw != 0 && H % 16 == 0 && (p2.slices == 1 || workspace != nullptr)) {
     void* out = p2.slices == 1 ? y_perm : workspace;
     if (launch_walk<MT, false>(p2, hw, expert_offsets, n_local, static_cast<const uint16_t*>(w_down),
-                               static_cast<const uint16_t*>(nullptr), H, I_s, out, cap_rows, RowMap{nullptr, 1}, stream)) {
+                               static_cast<const uint16_t*>(nullptr), H, I_s, out, cap_rows, RowMap{nullptr, 1},
+                               (flags & MOE_FFN_LEAVE_ROOM) != 0, stream)) {
       hipError_t err = hipGetLastError();
       if (err != hipSuccess || p2.slices == 1) return err;
       hipLaunchKernelGGL(gw::sum_slices_kernel, dim3(64), dim3(256), 0, stream, static_cast<const float*>(workspace),

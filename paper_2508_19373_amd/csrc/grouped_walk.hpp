@@ -4,9 +4,10 @@
 // Inference": the decoding stage is memory-bound by weight loading).  Measured on MI355X, a
 // kernel that re-reads the activation rows for every weight strip loses 10-40 % of the HBM
 // rate to the extra L1 requests, so here the activations never leave the register file:
-//  * a workgroup owns (expert, contiguous range of 16-feature strips, K slice); wavefront w
-//    owns k32 steps [w*STEPS, (w+1)*STEPS) of that slice and loads its MFMA A operands (the up
-//    to 16*MT activation rows, padded by clamping) ONCE, before walking the strips;
+//  * a workgroup owns a contiguous range of the list of (expert, pass of 16*MT rows, 16-feature
+//    strip) of one K slice; wavefront w owns k32 steps [w*STEPS, (w+1)*STEPS) of that slice and
+//    loads its MFMA A operands (the pass's activation rows, padded by clamping) ONCE per
+//    (expert, pass), before walking the strips;
 //  * the weights then flow as one continuous stream of 1 KB loads (16 rows x 64 contiguous
 //    bytes, the pattern that measured best: ~6.4 TB/s) through a register ring RING loads deep,
 //    crossing strip boundaries without draining;
@@ -14,7 +15,7 @@
 //    area (one barrier per strip) and are summed in wave order, so the result is deterministic;
 //  * K slices (grid.z > 1, down projection only) write fp32 partial outputs that a small
 //    second kernel adds in slice order;
-//  * experts without rows exit before touching their weights.
+//  * experts without rows have no entry in the list: their weights are never touched.
 #pragma once
 #include <type_traits>
 
@@ -51,7 +52,7 @@ constexpr int ring_size(int n) {
 
 // MT = 1 is compiled for 4 wavefronts per SIMD (at most 128 VGPRs: two 8-wave workgroups per CU),
 // MT = 2 for 2 per SIMD.
-// grid = (strip ranges, n_local, K slices).  GATEUP: Wa = gate, Wb = up, C = h (bf16).
+// grid = (workgroups per K slice, 1, K slices).  GATEUP: Wa = gate, Wb = up, C = h (bf16).
 // Else Wa = down and C = y (fp32) or, with K slices, the partial buffer [slice][cap_rows][n_out].
 template <int NW, int STEPS, int MT, bool GATEUP>
 __global__ __launch_bounds__(NW * 64, (MT == 1 ? 4 : 2)) void grouped_walk_kernel(

@@ -37,6 +37,17 @@ def _pad_inter(w_gate, w_up, w_down, inter_slice):
     return g, u, d, inter_slice + pad
 
 
+_SIDE_STREAMS = {}
+
+
+def _side_stream(device):
+    """One second stream per device for every layer of the process (layers run one after the other)."""
+    key = str(torch.device(device))
+    if key not in _SIDE_STREAMS:
+        _SIDE_STREAMS[key] = torch.cuda.Stream(device=device)
+    return _SIDE_STREAMS[key]
+
+
 class ExpertShardLayer:
     """route -> permute -> expert FFN (-> shared expert FFN) -> combine, on the current stream.
 
@@ -74,7 +85,7 @@ class ExpertShardLayer:
         # I_s = 12000 (Mixtral unsharded, I_s = 14336: permute -14 us, GEMM1 +16 us).
         self.gather_in_ffn = (inter_slice < 12288) if gather_in_ffn is None else bool(gather_in_ffn)
         self.overlap_shared = bool(overlap_shared) and shared is not None
-        self._side = torch.cuda.Stream(device=device) if self.overlap_shared else None
+        self._side = _side_stream(device) if self.overlap_shared else None
         self.Tmax = -1
         if max_tokens:
             self._alloc(max_tokens)
@@ -124,15 +135,15 @@ class ExpertShardLayer:
         yflag = B.MOE_Y_PERM_BF16 if self.y_perm_bf16 else 0
         rflag = yflag
         gateup_tiles = self.ffn_shard.n_local_experts * ((self.ffn_shard.inter_slice + 127) // 128)
-        if (self.shared is not None and self.overlap_shared and gateup_tiles >= 512
-                and not all(B.moe_debug_ffn_plan(T, self.shared_shard)[:2])):
+        if self.shared is not None and self.overlap_shared and not all(B.moe_debug_ffn_plan(T, self.shared_shard)[:2]):
             # a tiled shared expert cannot start beside resident weight-streaming workgroups (each
             # tiled workgroup needs a compute unit's whole LDS): keep the routed experts tiled too,
             # so that the two streams interleave tile by tile.  Measured: -8 to -20 % at 64 to 256
             # tokens on shards with 60 or 64 local experts (two or more rounds of tiles even with a
             # few rows per expert, so the tiled kernels stream as fast as the streaming kernel);
-            # +5 to +16 % on shards with 15 or 30 experts, hence the tile count.
-            rflag |= B.MOE_FFN_TILED
+            # +5 to +16 % on shards with 15 or 30 experts, hence the tile count.  Those leave 16
+            # compute units to the shared expert instead (30 experts, 96 / 128 tokens: 177 / 179 -> 170 / 173 us).
+            rflag |= B.MOE_FFN_TILED if gateup_tiles >= 512 else B.MOE_FFN_LEAVE_ROOM
         y_shared, joined = None, None
         if self.shared is not None:
             if getattr(self, "_sh_T", None) != T:

@@ -64,7 +64,7 @@ def test_header_constants_match_binding():
         m = re.search(name + r"\s*=\s*(-?\d+)", src)
         assert int(m.group(1)) == getattr(B, name)
     for name in ("MOE_RENORM_TOPK", "MOE_LOGITS_GIVEN", "MOE_Y_PERM_BF16", "MOE_OUT_F32", "MOE_FFN_SKIP_GATEUP",
-                 "MOE_FFN_SKIP_DOWN", "MOE_FFN_TILED"):
+                 "MOE_FFN_SKIP_DOWN", "MOE_FFN_TILED", "MOE_FFN_LEAVE_ROOM"):
         m = re.search(name + r"\s*=\s*1u\s*<<\s*(\d+)", src)
         assert 1 << int(m.group(1)) == getattr(B, name)
     assert ctypes.sizeof(B.MoeShard) == 24

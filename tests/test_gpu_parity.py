@@ -218,6 +218,9 @@ def test_expert_ffn_streaming_kernel_with_experts_that_need_several_row_passes()
     y = _ffn_gpu(xp, offs, shard, wg, wu, wd)
     assert np.all(np.isnan(y[R:]))
     assert _rel(y[:R], ref) < REL_L2 and np.abs(y[:R] - ref).max() < MAX_ABS
+    # with a sixteenth of the workgroups left out the ranges fall elsewhere; every sum keeps its order
+    yl = _ffn_gpu(xp, offs, shard, wg, wu, wd, flags=B.MOE_FFN_LEAVE_ROOM)
+    assert np.array_equal(yl[:R], y[:R]) and np.all(np.isnan(yl[R:]))
     # the same call on the tiled kernels
     yt = _ffn_gpu(xp, offs, shard, wg, wu, wd, flags=B.MOE_FFN_TILED)
     assert np.all(np.isnan(yt[R:]))
