@@ -55,11 +55,6 @@ def measure(shape, tokens, seed=0, steps=60, warmup=30):
     from .layer import ExpertShardLayer, bf16_tensor
     from .work import algorithmic_work
 
-    # every shard starts from freshly allocated device memory: weights carved out of blocks that a
-    # larger, earlier shard left in torch's caching allocator measured 3-8 % slower in the decoding regime
-    import gc
-    gc.collect()
-    torch.cuda.empty_cache()
     li = I.make_layer_inputs(shape, 1, seed)
     layer = ExpertShardLayer.from_inputs(li, max_tokens=max(tokens))
     rows = []
@@ -69,15 +64,20 @@ def measure(shape, tokens, seed=0, steps=60, warmup=30):
         if shape.router == "zipf":
             logits = torch.from_numpy(I.make_zipf_logits(seed, T, shape.n_experts)).cuda()
 
-        def timed(fn):
+        def timed(fn, batches=3):
+            # median of three timed batches: a single batch of a 100 us layer lasts a few
+            # milliseconds, and one in twenty of those came out 10-15 % off
             for _ in range(warmup):
                 fn()
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(steps):
-                fn()
-            torch.cuda.synchronize()
-            return (time.perf_counter() - t0) * 1e6 / steps
+            out = []
+            for _ in range(batches):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(steps):
+                    fn()
+                torch.cuda.synchronize()
+                out.append((time.perf_counter() - t0) * 1e6 / steps)
+            return sorted(out)[len(out) // 2]
 
         # a shard whose weights fit the last-level cache (256 MB) would be served from it when the same
         # buffers are replayed; in a model every layer has its own weights.  Rotate over copies
@@ -128,18 +128,36 @@ def main():
     ap.add_argument("--out", required=True)
     ap.add_argument("--tokens", type=int, nargs="*", default=list(DEFAULT_TOKENS))
     ap.add_argument("--models", nargs="*", default=["mixtral", "qwen", "qwen2_57b"])
+    ap.add_argument("--shard", default=None, help="MODEL:TP:EP, measure this one shard in this process")
     args = ap.parse_args()
     bases = {"mixtral": I.MIXTRAL, "qwen": I.QWEN, "qwen2_57b": I.QWEN2_57B}
+
+    def write(rows):
+        with open(args.out, "w", newline="") as f:
+            w = csv.DictWriter(f, fieldnames=FIELDS)
+            w.writeheader()
+            w.writerows(rows)
+
+    if args.shard is not None:
+        m, tp, ep = args.shard.split(":")
+        write(measure(bases[m].shard(tp_degree=int(tp), tp_rank=0, ep_degree=int(ep), ep_rank=0), args.tokens))
+        return
+    # One child process per shard (this one never touches the GPU).  In the memory-bound regime a
+    # layer whose weights were allocated after a larger layer was freed, from torch's cache or anew,
+    # measured 3-10 % slower than the same layer in a fresh process; a model is loaded once.
+    import os
+    import subprocess
+    import tempfile
     rows = []
     for m in args.models:
-        base = bases[m]
-        for tp, ep in legal_shards(base):
-            shape = base.shard(tp_degree=tp, tp_rank=0, ep_degree=ep, ep_rank=0)
-            rows += measure(shape, args.tokens)
-    with open(args.out, "w", newline="") as f:
-        w = csv.DictWriter(f, fieldnames=FIELDS)
-        w.writeheader()
-        w.writerows(rows)
+        for tp, ep in legal_shards(bases[m]):
+            with tempfile.TemporaryDirectory() as d:
+                part = os.path.join(d, "part.csv")
+                subprocess.run([sys.executable, "-m", "paper_2508_19373_amd.latency_table", "--out", part, "--shard",
+                                "%s:%d:%d" % (m, tp, ep), "--tokens", *[str(t) for t in args.tokens]], check=True)
+                with open(part, newline="") as f:
+                    rows += list(csv.DictReader(f))
+    write(rows)
     print("wrote %d rows to %s" % (len(rows), args.out))
 
 
