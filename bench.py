@@ -166,10 +166,12 @@ def main():
     br = {}
     br["route_topk"] = time_events(lambda: B.moe_route_topk(x, layer.w_router, layer.logits, T, H, E, k, rflags,
                                                             layer.topk_idx, layer.topk_w), it, torch)
-    br["permute"] = time_events(lambda: B.moe_permute(x, layer.topk_idx, T, k, layer.shard, layer.x_perm,
+    gather = layer.gathers(T)
+    br["permute"] = time_events(lambda: B.moe_permute(x, layer.topk_idx, T, k, layer.shard,
+                                                      None if gather else layer.x_perm,
                                                       layer.expert_offsets, layer.row_src, layer.slot_row,
                                                       layer.workspace), it, torch)
-    if layer.gather_in_ffn:   # the routed experts read their rows of x in place
+    if gather:   # the routed experts read their rows of x in place
         ffn = lambda fl: B.moe_expert_ffn_gather(x, layer.row_src, k, layer.expert_offsets, T * k, layer.shard,
                                                  layer.w_gate, layer.w_up, layer.w_down, layer.h_ws, layer.y_perm,
                                                  layer.ffn_ws, fl)

@@ -82,8 +82,11 @@ class ExpertShardLayer:
         # the routed experts can read their rows of x in place through row_src (no permuted copy of
         # x).  That saves about half of moe_permute's time and costs about 1 % of GEMM1's (scattered
         # rows), so by default it is used unless the slice is wide: measured break-even near
-        # I_s = 12000 (Mixtral unsharded, I_s = 14336: permute -14 us, GEMM1 +16 us).
+        # I_s = 12000 (Mixtral unsharded, I_s = 14336: permute -14 us, GEMM1 +16 us).  The weight-streaming
+        # kernel loads its rows once per workgroup either way, so calls that it serves always gather
+        # (gathers(T) below).
         self.gather_in_ffn = (inter_slice < 12288) if gather_in_ffn is None else bool(gather_in_ffn)
+        self._gather_auto = gather_in_ffn is None
         self.overlap_shared = bool(overlap_shared) and shared is not None
         self._side = _side_stream(device) if self.overlap_shared else None
         self.Tmax = -1
@@ -114,6 +117,12 @@ class ExpertShardLayer:
             self.ffn_ws_sh = torch.empty(max(B.moe_ffn_workspace_bytes(Tn, self.shared_shard), 256),
                                          dtype=torch.uint8, device=d)
         self.Tmax = T
+
+    def gathers(self, T) -> bool:
+        """Whether a forward of T tokens reads the routed experts' rows of x in place (no permuted copy)."""
+        if self.gather_in_ffn or not self._gather_auto:
+            return self.gather_in_ffn
+        return bool(B.moe_debug_ffn_plan(T * self.k, self.ffn_shard)[0])   # GEMM1 on the streaming kernel
 
     def forward(self, x: torch.Tensor, logits: torch.Tensor | None = None, stream=None) -> torch.Tensor:
         T = x.shape[0]
@@ -161,9 +170,10 @@ class ExpertShardLayer:
                              self.h_sh, self.y_shared, self.ffn_ws_sh, yflag, self._side)
             joined = self._side
         B.moe_route_topk(x, self.w_router, self.logits, T, H, E, k, flags, self.topk_idx, self.topk_w, stream)
-        B.moe_permute(x, self.topk_idx, T, k, self.shard, self.x_perm, self.expert_offsets, self.row_src,
-                      self.slot_row, self.workspace, stream=stream)
-        if self.gather_in_ffn:
+        gather = self.gathers(T)
+        B.moe_permute(x, self.topk_idx, T, k, self.shard, None if gather else self.x_perm, self.expert_offsets,
+                      self.row_src, self.slot_row, self.workspace, stream=stream)
+        if gather:
             B.moe_expert_ffn_gather(x, self.row_src, k, self.expert_offsets, T * k, self.ffn_shard, self.w_gate,
                                     self.w_up, self.w_down, self.h_ws, self.y_perm, self.ffn_ws, rflag, stream)
         else:
