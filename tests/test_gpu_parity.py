@@ -48,6 +48,11 @@ def _route_gpu(x_bits, w_router, logits, T, H, E, k, renorm):
 @pytest.mark.parametrize("shape,T", [(I.TINY, 64), (I.MoEShape("q", 256, 60, 4, 128, False), 77),
                                      (I.MoEShape("wide", 128, 200, 6, 128, True), 33),
                                      (I.MoEShape("odd", 64, 13, 3, 128, True), 5),
+                                     # up to 16 experts: W_r goes through the wavefronts' LDS areas
+                                     (I.MoEShape("e3", 96, 3, 2, 128, True), 37),
+                                     (I.MoEShape("e9", 4096, 9, 2, 128, True), 16),
+                                     (I.MoEShape("e16", 2080, 16, 4, 128, False), 150),
+                                     (I.MoEShape("e8", 4096, 8, 2, 128, True), 1),
                                      (I.MoEShape("max", 192, 256, 16, 128, False), 40),    # E and k at their limits
                                      # more than 128 tokens: logits and selection in one kernel, 2 to 16 expert tiles
                                      (I.MoEShape("q2", 256, 30, 4, 128, False), 300),
