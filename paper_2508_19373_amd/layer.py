@@ -166,8 +166,11 @@ class ExpertShardLayer:
                 raise ValueError("overlap_shared works on torch's current stream only")
             main = torch.cuda.current_stream()
             self._side.wait_stream(main)          # x (and sh_offsets) are ready where main stands now
+            # a streaming shared expert leaves 16 compute units free, so that the router and the
+            # permutation on the main stream, each a workgroup or two on the critical path, start
+            # at once instead of waiting for a resident workgroup to finish (-2 to -3.5 % at 16 to 64 tokens)
             B.moe_expert_ffn(x, self.sh_offsets, T, self.shared_shard, self.shared[0], self.shared[1], self.shared[2],
-                             self.h_sh, self.y_shared, self.ffn_ws_sh, yflag, self._side)
+                             self.h_sh, self.y_shared, self.ffn_ws_sh, yflag | B.MOE_FFN_LEAVE_ROOM, self._side)
             joined = self._side
         B.moe_route_topk(x, self.w_router, self.logits, T, H, E, k, flags, self.topk_idx, self.topk_w, stream)
         gather = self.gathers(T)
