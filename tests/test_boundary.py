@@ -140,6 +140,10 @@ def test_expert_ffn_validation(lib):
     assert f(P, P, 8, ctypes.byref(_shard(inter_full=1000, inter_slice=500)), P, P, P, P, P, P, W, 0, None) \
         == B.MOE_ERR_UNSUPPORTED_SHAPE
     assert f(P, P, 8, ctypes.byref(s), P, P, P + 8, P, P, P, W, 0, None) == B.MOE_ERR_INVALID_ARG
+    # the scheduling hints are accepted (an empty call: nothing is launched), unknown bits are not
+    hints = B.MOE_FFN_TILED | B.MOE_FFN_LEAVE_ROOM
+    assert f(P, P, 0, ctypes.byref(s), P, P, P, P, P, P, W, hints, None) == B.MOE_OK
+    assert f(P, P, 0, ctypes.byref(s), P, P, P, P, P, P, W, 1 << 8, None) == B.MOE_ERR_INVALID_ARG
     # decode-sized call on a Mixtral-shaped shard needs split-K scratch; a prefill-sized one room for the
     # partial sums of tiles cut along K (65536 / 16 column blocks rows, whatever the capacity)
     mix = _shard(hidden=4096, inter_full=14336, inter_slice=14336)
