@@ -108,9 +108,6 @@ def test_sliced_work_list_covers_every_tile_and_slice_once(E_loc, hidden, inter,
             counts = (counts // 256) * 256          # no remainder tiles
         offs = _offsets(counts)
         (keep_rb, slices, rows, scratch), units = B.moe_debug_down_slices(offs, cap, shard, with_units=True)
-        plain = B.moe_debug_gemm_units(offs, cap, ncb)
-        tiles = {(int(h), int(e), int(r0), int(nb)) for h, e, r0, _, nb in plain if h}
-        assert len(tiles) == (plain[:, 0] > 0).sum()
         if nk < 16:
             assert slices == 1
         n_sliced_cases += slices > 1
@@ -119,8 +116,25 @@ def test_sliced_work_list_covers_every_tile_and_slice_once(E_loc, hidden, inter,
             pad = 128 if (c >= 256 or pad_low) else 192
             r = c % 256
             return c // 256 + (r > pad), int(64 < r <= pad) + int(0 < r <= 64 or 128 < r <= pad)
-        pad_low = sum(sum(blocks(c, False)) for c in counts) * ncb >= 256     # the launch fills the chip
+        # a down projection that may be cut along K pads a remainder above 128 rows to a 256-row
+        # block whatever the launch size; one that cannot (short K) only when the launch fills the chip
+        pad_low = nk >= 16 or sum(sum(blocks(c, False)) for c in counts) * ncb >= 256
         first_rb = np.concatenate([[0], np.cumsum([blocks(c, pad_low)[0] for c in counts])])
+        # the tiles that have to exist, from the row-block rule written out
+        tiles = set()
+        for e, c in enumerate(counts):
+            c, r, pad = int(c), int(c) % 256, 128 if (c >= 256 or pad_low) else 192
+            heights = [256] * (c // 256 + (r > pad))
+            if r <= pad:
+                heights += [128] * int(r > 64) + [64] * int(0 < r <= 64 or r > 128)
+            r0 = int(offs[e])
+            for h in heights:
+                tiles |= {(h, e, r0, nb) for nb in range(ncb)}
+                r0 += h
+        if not pad_low or nk < 16:
+            plain = B.moe_debug_gemm_units(offs, cap, ncb)
+            if (sum(sum(blocks(c, False)) for c in counts) * ncb >= 256) == pad_low:
+                assert tiles == {(int(h), int(e), int(r0), int(nb)) for h, e, r0, _, nb in plain if h}
         seen = {}
         scratch_cells = set()
         for h, e, r0, nb, z, kt0, n, srow in units:
