@@ -48,13 +48,13 @@ struct ClassCounts {
   bool pad_low;
 };
 constexpr int kPadLowTiles = 256;
-// The sliced down projection pads from 64 tiles on (kPadAlways, named for what it means at the
-// shapes of interest): its tiles are cut along K until they fill the chip anyway, so 128 + 64 rows
+// The sliced down projection pads from 64 tiles on: its tiles are cut along K until they fill the
+// chip anyway, so 128 + 64 rows
 // only stream an expert's weights twice (Mixtral at 128 to 200 rows per expert: 224 tiles, below
 // kPadLowTiles; down projection 262 / 311 us at 512 / 768 tokens against 171 us at 384).  Below 64
 // tiles the padded launch would need more than 8 slices per tile to fill the chip, and such short
 // walks are mostly fixed cost (a single expert of 192 rows: layer 150 -> 157 us when padded).
-constexpr int kPadAlways = 64;
+constexpr int kPadSlicedTiles = 64;
 __host__ __device__ inline ClassCounts count_tiles(const int32_t* __restrict__ expert_offsets, int n_local,
                                                    int n_col_blocks, int pad_from = kPadLowTiles) {
   ClassCounts c = {{0, 0, 0}, false};
