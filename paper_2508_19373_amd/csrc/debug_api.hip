@@ -55,7 +55,7 @@ extern "C" int32_t moe_debug_down_slices(const int32_t* expert_offsets, int32_t 
   using namespace moe::gg;
   const int ncb = (shard->hidden + 255) / 256, nk = shard->inter_slice / 64;
   const SlicePlan sp = slice_plan(cap_rows, ncb, shard->inter_slice);
-  const ClassCounts cc = count_tiles(expert_offsets, n_local, ncb, sp.max_slices > 1 ? kPadSlicedTiles : kPadLowTiles);
+  const ClassCounts cc = count_tiles(expert_offsets, n_local, ncb, sp.max_slices > 1 ? sliced_pad_from(nk) : kPadLowTiles);
   const SliceChoice sc = choose_slices(cc, ncb, nk, sp.max_slices);
   slices[0] = sc.keep_rb;
   slices[1] = sc.slices;

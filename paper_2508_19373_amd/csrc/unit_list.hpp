@@ -48,13 +48,16 @@ struct ClassCounts {
   bool pad_low;
 };
 constexpr int kPadLowTiles = 256;
-// The sliced down projection pads from 64 tiles on: its tiles are cut along K until they fill the
-// chip anyway, so 128 + 64 rows
-// only stream an expert's weights twice (Mixtral at 128 to 200 rows per expert: 224 tiles, below
-// kPadLowTiles; down projection 262 / 311 us at 512 / 768 tokens against 171 us at 384).  Below 64
-// tiles the padded launch would need more than 8 slices per tile to fill the chip, and such short
-// walks are mostly fixed cost (a single expert of 192 rows: layer 150 -> 157 us when padded).
-constexpr int kPadSlicedTiles = 64;
+// The sliced down projection pads from 128 tiles on (sliced_pad_from): its tiles are cut along K until they fill the
+// chip anyway, so 128 + 64 rows only stream an expert's weights twice (Mixtral at 128 to 200 rows
+// per expert: 224 tiles, below kPadLowTiles; down projection 262 / 311 us at 512 / 768 tokens
+// against 171 us at 384).  With fewer tiles the padded launch needs so many slices per tile to
+// fill the chip that the walks are mostly fixed cost (192 rows per expert: one expert, 32 tiles,
+// layer 150 -> 157 us when padded; two experts, 64 tiles, 225 -> 228 us; four, 128 tiles, 430 -> 393 us).
+// Nor does it pay on a short K (below 48 k-tiles): there is little to re-stream, and the two slices
+// that 128 padded tiles allow are short (Mixtral TP=8, 28 k-tiles: layer 151 -> 162 us at 512 tokens,
+// 179 -> 172 us at 768).
+__host__ __device__ inline int sliced_pad_from(int nk) { return nk >= 48 ? 128 : kPadLowTiles; }
 __host__ __device__ inline ClassCounts count_tiles(const int32_t* __restrict__ expert_offsets, int n_local,
                                                    int n_col_blocks, int pad_from = kPadLowTiles) {
   ClassCounts c = {{0, 0, 0}, false};

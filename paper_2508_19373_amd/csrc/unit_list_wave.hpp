@@ -189,7 +189,7 @@ __device__ inline WaveSlicedUnit wave_find_sliced_unit(const int32_t* __restrict
                                                        int n_col_blocks, int nk_all, int max_slices, int bid) {
   WaveSlicedUnit r;
   r.valid = false;
-  const WaveRouting w = wave_routing(expert_offsets, n_local, n_col_blocks, kPadSlicedTiles);
+  const WaveRouting w = wave_routing(expert_offsets, n_local, n_col_blocks, sliced_pad_from(nk_all));
   const SliceChoice sc = choose_slices(w.cc, n_col_blocks, nk_all, max_slices);
   const SlicedUnit u = find_sliced_unit(w.cc, sc, n_col_blocks, bid);
   if (u.cls < 0) return r;
@@ -248,7 +248,7 @@ __device__ inline WaveSlicedUnit find_sliced_unit_of(const int32_t* __restrict__
     return wave_find_sliced_unit(expert_offsets, n_local, n_col_blocks, nk_all, max_slices, bid);
   WaveSlicedUnit r;
   r.valid = false;
-  const ClassCounts cc = count_tiles(expert_offsets, n_local, n_col_blocks, kPadSlicedTiles);
+  const ClassCounts cc = count_tiles(expert_offsets, n_local, n_col_blocks, sliced_pad_from(nk_all));
   const SliceChoice sc = choose_slices(cc, n_col_blocks, nk_all, max_slices);
   const SlicedUnit u = find_sliced_unit(cc, sc, n_col_blocks, bid);
   if (u.cls < 0) return r;
@@ -287,14 +287,14 @@ __device__ inline SumPlan sum_plan(const int32_t* __restrict__ expert_offsets, i
   p.total = 0;
   p.pad_low = false;
   if (p.plain) {
-    const ClassCounts cc = count_tiles(expert_offsets, n_local, n_col_blocks, kPadSlicedTiles);
+    const ClassCounts cc = count_tiles(expert_offsets, n_local, n_col_blocks, sliced_pad_from(nk_all));
     const SliceChoice sc = choose_slices(cc, n_col_blocks, nk_all, max_slices);
     p.slices = sc.slices;
     p.keep_rb = sc.keep_rb;
     p.pad_low = cc.pad_low;
     if (sc.slices > 1) p.total = sliced_rows(expert_offsets, n_local, 0, sc.keep_rb, cc.pad_low).total;
   } else {
-    p.w = wave_routing(expert_offsets, n_local, n_col_blocks, kPadSlicedTiles);
+    p.w = wave_routing(expert_offsets, n_local, n_col_blocks, sliced_pad_from(nk_all));
     const SliceChoice sc = choose_slices(p.w.cc, n_col_blocks, nk_all, max_slices);
     p.slices = sc.slices;
     p.keep_rb = sc.keep_rb;

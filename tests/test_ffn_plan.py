@@ -117,8 +117,8 @@ def test_sliced_work_list_covers_every_tile_and_slice_once(E_loc, hidden, inter,
             r = c % 256
             return c // 256 + (r > pad), int(64 < r <= pad) + int(0 < r <= 64 or 128 < r <= pad)
         # a down projection that may be cut along K pads a remainder above 128 rows to a 256-row
-        # block from 64 tiles on; one that cannot (short K) only when the launch fills the chip
-        pad_low = sum(sum(blocks(c, False)) for c in counts) * ncb >= (64 if nk >= 16 else 256)
+        # block from 128 tiles on if K is at least 48 k-tiles; otherwise only when the launch fills the chip
+        pad_low = sum(sum(blocks(c, False)) for c in counts) * ncb >= (128 if nk >= 48 else 256)
         first_rb = np.concatenate([[0], np.cumsum([blocks(c, pad_low)[0] for c in counts])])
         # the tiles that have to exist, from the row-block rule written out
         tiles = set()
