@@ -187,6 +187,8 @@ def _ffn_gpu(x_perm_bits, offs, shard, wg, wu, wd, y_bf16=False, gather=None, fl
     (256, 320, [64, 128, 21, 256]),                  # four and five k-tiles, all three tile heights
     (512, 4096, [2000]),                             # one expert, few column blocks, long K: down projection in 8 K slices
     (256, 2048, [700, 0, 900]),                      # ... in 4 K slices, with remainder tiles and an empty expert
+    # 129 to 192 rows per expert, 128 tiles, K = 48 k-tiles: the sliced down projection pads them to 256-row tiles
+    (1024, 3072, [130, 192, 150, 129, 0, 64, 191, 140, 160, 131, 170, 5, 188, 145, 133, 177, 190, 139]),
 ])
 def test_expert_ffn_against_oracle(H, I_s, counts):
     n = len(counts)
