@@ -48,6 +48,23 @@ def _side_stream(device):
     return _SIDE_STREAMS[key]
 
 
+def routed_hint_beside_shared(ffn_shard, shared_shard, T) -> int:
+    """Scheduling hint (a moe_expert_ffn flag, or 0) for the routed experts' call when the shared
+    expert of T tokens runs beside it on a second stream.
+
+    A tiled shared expert cannot start beside resident weight-streaming workgroups (each tiled
+    workgroup needs a compute unit's whole LDS): the routed experts are kept tiled too, so that the
+    two streams interleave tile by tile.  Measured: -8 to -20 % at 64 to 256 tokens on shards with
+    60 or 64 local experts (two or more rounds of tiles even with a few rows per expert, so the
+    tiled kernels stream as fast as the streaming kernel); +5 to +16 % on shards with 15 or 30
+    experts, hence the tile count.  Those leave 16 compute units to the shared expert instead (30
+    experts, 96 / 128 tokens: 177 / 179 -> 170 / 173 us).  A streaming shared expert needs neither."""
+    if all(B.moe_debug_ffn_plan(T, shared_shard)[:2]):
+        return 0
+    gateup_tiles = ffn_shard.n_local_experts * ((ffn_shard.inter_slice + 127) // 128)
+    return B.MOE_FFN_TILED if gateup_tiles >= 512 else B.MOE_FFN_LEAVE_ROOM
+
+
 class ExpertShardLayer:
     """route -> permute -> expert FFN (-> shared expert FFN) -> combine, on the current stream.
 
@@ -143,16 +160,8 @@ class ExpertShardLayer:
             flags |= B.MOE_LOGITS_GIVEN
         yflag = B.MOE_Y_PERM_BF16 if self.y_perm_bf16 else 0
         rflag = yflag
-        gateup_tiles = self.ffn_shard.n_local_experts * ((self.ffn_shard.inter_slice + 127) // 128)
-        if self.shared is not None and self.overlap_shared and not all(B.moe_debug_ffn_plan(T, self.shared_shard)[:2]):
-            # a tiled shared expert cannot start beside resident weight-streaming workgroups (each
-            # tiled workgroup needs a compute unit's whole LDS): keep the routed experts tiled too,
-            # so that the two streams interleave tile by tile.  Measured: -8 to -20 % at 64 to 256
-            # tokens on shards with 60 or 64 local experts (two or more rounds of tiles even with a
-            # few rows per expert, so the tiled kernels stream as fast as the streaming kernel);
-            # +5 to +16 % on shards with 15 or 30 experts, hence the tile count.  Those leave 16
-            # compute units to the shared expert instead (30 experts, 96 / 128 tokens: 177 / 179 -> 170 / 173 us).
-            rflag |= B.MOE_FFN_TILED if gateup_tiles >= 512 else B.MOE_FFN_LEAVE_ROOM
+        if self.shared is not None and self.overlap_shared:
+            rflag |= routed_hint_beside_shared(self.ffn_shard, self.shared_shard, T)
         y_shared, joined = None, None
         if self.shared is not None:
             if getattr(self, "_sh_T", None) != T:

@@ -187,3 +187,17 @@ def test_invalid_arguments():
     assert L.moe_debug_ffn_plan(-1, ctypes.byref(s), plan) == B.MOE_ERR_INVALID_ARG
     assert L.moe_debug_ffn_plan(8, None, plan) == B.MOE_ERR_INVALID_ARG
     assert L.moe_debug_ffn_plan(8, ctypes.byref(s), None) == B.MOE_ERR_INVALID_ARG
+
+
+def test_hint_for_routed_experts_beside_an_overlapped_shared_expert():
+    from paper_2508_19373_amd.layer import routed_hint_beside_shared as hint
+    shared = _shard(1, 1, hidden=2048, inter_full=5632, inter_slice=5632)       # Qwen1.5-MoE's shared expert
+    full = _shard(60, 60, hidden=2048, inter_full=1408, inter_slice=1408)      # 60 x 11 = 660 gate/up tiles
+    ep2 = _shard(60, 30, hidden=2048, inter_full=1408, inter_slice=1408)       # 330
+    tp2ep4 = _shard(60, 15, hidden=2048, inter_full=1408, inter_slice=704)     # 90
+    for T in (16, 32):                                                           # the shared expert streams: no hint
+        assert hint(full, shared, T) == 0 and hint(ep2, shared, T) == 0
+    for T in (64, 96, 256, 4096):                                                # the shared expert has a tiled GEMM
+        assert hint(full, shared, T) == B.MOE_FFN_TILED
+        assert hint(ep2, shared, T) == B.MOE_FFN_LEAVE_ROOM
+        assert hint(tp2ep4, shared, T) == B.MOE_FFN_LEAVE_ROOM
