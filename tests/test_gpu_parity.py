@@ -53,6 +53,10 @@ def _route_gpu(x_bits, w_router, logits, T, H, E, k, renorm):
                                      (I.MoEShape("e9", 4096, 9, 2, 128, True), 16),
                                      (I.MoEShape("e16", 2080, 16, 4, 128, False), 150),
                                      (I.MoEShape("e8", 4096, 8, 2, 128, True), 1),
+                                     # up to 64 tokens with 8 experts: one workgroup per token on the vector units
+                                     (I.MoEShape("e8s", 4096, 8, 2, 128, True), 64),
+                                     (I.MoEShape("e16s", 2080, 16, 4, 128, False), 40),
+                                     (I.MoEShape("e16t", 72, 16, 16, 128, True), 3),
                                      (I.MoEShape("max", 192, 256, 16, 128, False), 40),    # E and k at their limits
                                      # more than 128 tokens: logits and selection in one kernel, 2 to 16 expert tiles
                                      (I.MoEShape("q2", 256, 30, 4, 128, False), 300),
