@@ -29,8 +29,8 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 # (FETCH_SIZE, WRITE_SIZE in KiB per dispatch; see profiles/<workload>_rocprofv3.txt), each scaled by
 # what the same counter reads for a plain 1 GiB device copy: FETCH_SIZE x 2.0, WRITE_SIZE x 1.0.
 MEASURED_TRAFFIC_BYTES = {
-    "mixtral_prefill": (1959095.9 * 2.0 + 232964.7) * 1024,
-    "mixtral_decode": (936910.6 * 2.0 + 898.7) * 1024,
+    "mixtral_prefill": (1958869.5 * 2.0 + 232964.5) * 1024,
+    "mixtral_decode": (936905.7 * 2.0 + 898.8) * 1024,
 }
 
 # name -> (inputs.WORKLOADS key, token count, description)
