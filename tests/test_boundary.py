@@ -188,3 +188,21 @@ def test_binding_refuses_host_tensors(lib):
     t = torch.zeros(4, 8)
     with pytest.raises(ValueError):
         B.moe_route_topk(t, t, t, 4, 8, 8, 2, 0, t, t, stream=0)
+
+
+def test_public_headers_are_plain_c(tmp_path):
+    """The boundary is a C ABI: every header under include/ compiles as C99 on its own."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    inc = os.path.join(ROOT, "include")
+    for name in sorted(os.listdir(inc)):
+        if not name.endswith(".h"):
+            continue
+        src = tmp_path / (name + ".c")
+        src.write_text('#include "%s"\nint main(void) { return 0; }\n' % name)
+        r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-c", str(src),
+                            "-o", str(tmp_path / (name + ".o"))], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
