@@ -139,6 +139,31 @@ def test_permute_bit_exact(T, k, E, n_local, off):
     assert np.all(row_src[R:] == -5)  # nothing written past R
 
 
+@pytest.mark.parametrize("T,k,E,n_local,off", [
+    (16, 2, 8, 8, 0), (32, 2, 8, 8, 0), (16, 4, 60, 60, 0), (16, 4, 60, 15, 30), (8, 8, 64, 64, 0), (4, 16, 256, 256, 0),
+    (4, 16, 256, 64, 128), (1, 1, 8, 8, 0), (33, 2, 8, 8, 0), (21, 3, 200, 200, 0), (30, 2, 8, 1, 7), (64, 1, 130, 130, 0)])
+def test_permute_index_arrays_alone(T, k, E, n_local, off):
+    """x_perm = NULL: only the index arrays are written."""
+    rng = np.random.default_rng(7 * T + k + E)
+    x = I.make_x(0, T, 64)
+    pop = I.zipf_popularity(E)
+    idx = np.stack([rng.choice(E, size=k, replace=False, p=pop) for _ in range(T)]).astype(np.int32)
+    shard = B.make_shard(E, n_local, off, 64, 128, 128)
+    cap = T * k
+    offs = torch.full((n_local + 1,), -5, dtype=torch.int32, device="cuda")
+    row_src = torch.full((cap,), -5, dtype=torch.int32, device="cuda")
+    slot_row = torch.full((cap,), -5, dtype=torch.int32, device="cuda")
+    ws = torch.empty(max(B.moe_workspace_bytes(T, k, shard), 1), dtype=torch.uint8, device="cuda")
+    B.moe_permute(None, _dev(idx), T, k, shard, None, offs, row_src, slot_row, ws)
+    torch.cuda.synchronize()
+    roffs, rrow_src, rslot_row, _ = O.permute(x, idx, n_local, off)
+    R = int(roffs[-1])
+    assert np.array_equal(offs.cpu().numpy(), roffs)
+    assert np.array_equal(row_src.cpu().numpy()[:R], rrow_src[:R])
+    assert np.all(row_src.cpu().numpy()[R:] == -5)          # entries past R are not touched
+    assert np.array_equal(slot_row.cpu().numpy(), rslot_row)
+
+
 def test_permute_is_deterministic():
     rng = np.random.default_rng(9)
     T, k, E, H = 3000, 4, 60, 64
