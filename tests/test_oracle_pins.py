@@ -321,3 +321,60 @@ def test_combine_zero_for_tokens_without_local_expert():
     w = np.array([[0.5, 0.25], [0.7, 0.3], [0.6, 0.4]])
     y = O.combine(y_perm, slot_row, w, 3, 2)
     assert np.allclose(y, [[0.25, 0.5, 0.75], [0, 0, 0], [2.4, 3.0, 3.6]])
+
+
+def _dense_mix(li, idx, w, experts_lo=0, n_local=None):
+    """sum_j w[t,j] * FFN_{idx[t,j]}(x_t) over the local experts, token by token, from hand-made
+    routing decisions (no logits, no softmax, no permutation)."""
+    x = I.bf16_bits_to_f32(li.x).astype(np.float64)
+    n_local = li.w_gate.shape[0] if n_local is None else n_local
+    y = np.zeros((x.shape[0], x.shape[1]))
+    for t in range(x.shape[0]):
+        for j in range(idx.shape[1]):
+            le = int(idx[t, j]) - experts_lo
+            if 0 <= le < n_local:
+                Wg = I.bf16_bits_to_f32(li.w_gate[le]).astype(np.float64)
+                Wu = I.bf16_bits_to_f32(li.w_up[le]).astype(np.float64)
+                Wd = I.bf16_bits_to_f32(li.w_down[le]).astype(np.float64)
+                g = Wg @ x[t]
+                y[t] += w[t, j] * (Wd @ (g * scipy.special.expit(g) * (Wu @ x[t])))
+    return y
+
+
+@pytest.mark.parametrize("renorm", [True, False])
+def test_layer_with_given_routing_equals_routed_call(renorm):
+    # the routing override is the branch the full-size GPU checks take: feeding it the decisions
+    # route_topk makes from the same logits must reproduce the routed call exactly, also on a
+    # token sample (each output row depends on its own token only) and on an expert-parallel shard
+    li, logits = _inputs(T=40)
+    idx, _, w64 = O.route_topk(logits, 3, renorm)
+    a = O.expert_layer(li.x, logits, 3, renorm, 8, 0, li.w_gate, li.w_up, li.w_down)
+    b = O.expert_layer(li.x, None, 3, renorm, 8, 0, li.w_gate, li.w_up, li.w_down, topk=(idx, w64))
+    assert np.array_equal(a, b)
+    sel = np.array([0, 3, 4, 17, 39])
+    c = O.expert_layer(li.x[sel], None, 3, renorm, 8, 0, li.w_gate, li.w_up, li.w_down, topk=(idx[sel], w64[sel]))
+    assert _rel(c, a[sel]) < 1e-13
+    g, u, d, n, off = O.ep_slice(li.w_gate, li.w_up, li.w_down, 4, 2)
+    e1 = O.expert_layer(li.x, logits, 3, renorm, n, off, g, u, d)
+    e2 = O.expert_layer(li.x[sel], None, 3, renorm, n, off, g, u, d, topk=(idx[sel], w64[sel]))
+    assert _rel(e2, e1[sel]) < 1e-13
+
+
+def test_layer_with_handmade_routing_equals_dense_mix():
+    # decisions no softmax would produce (weights that do not sum to one, a negative one, repeated
+    # use of one expert by neighbouring tokens): the override must take them as given
+    li, _ = _inputs(T=12)
+    rng = np.random.default_rng(5)
+    idx = np.stack([rng.permutation(8)[:2] for _ in range(12)]).astype(np.int32)
+    idx[3] = idx[4] = idx[5] = (7, 0)
+    w = rng.uniform(-0.5, 1.5, size=(12, 2))
+    y = O.expert_layer(li.x, None, 2, False, 8, 0, li.w_gate, li.w_up, li.w_down, topk=(idx, w))
+    assert _rel(y, _dense_mix(li, idx, w)) < 1e-12
+    # swapping the two slots of every token changes nothing but the summation order
+    y2 = O.expert_layer(li.x, None, 2, False, 8, 0, li.w_gate, li.w_up, li.w_down, topk=(idx[:, ::-1], w[:, ::-1]))
+    assert _rel(y2, y) < 1e-13
+    # an expert-parallel shard keeps only its experts' terms
+    g, u, d, n, off = O.ep_slice(li.w_gate, li.w_up, li.w_down, 2, 1)
+    ys = O.expert_layer(li.x, None, 2, False, n, off, g, u, d, topk=(idx, w))
+    li_s = type("S", (), {"x": li.x, "w_gate": g, "w_up": u, "w_down": d})
+    assert _rel(ys, _dense_mix(li_s, idx, w, experts_lo=off, n_local=n)) < 1e-12
