@@ -1,7 +1,8 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
 Integer outputs (top-k ids, offsets, permutation, permuted rows) are checked in full against
-the oracle; the layer output is checked on a random sample of tokens with every hidden column
-(each output row depends only on its own token, so a sample of rows is a valid check)."""
+the oracle; the layer output is checked, with every hidden column, on all tokens of a small batch
+and otherwise on at least 512 random tokens plus the tokens that own the rows at the edges of the
+kernels' work units for that routing (tests/sampling.py)."""
 import numpy as np
 import pytest
 import torch
@@ -10,12 +11,18 @@ from oracle import moe_oracle as O
 from paper_2508_19373_amd import binding as B
 from paper_2508_19373_amd import inputs as I
 from paper_2508_19373_amd.layer import ExpertShardLayer, bf16_bits, bf16_tensor
+from sampling import stratified_tokens
 
 pytestmark = pytest.mark.gpu
 
 REL_L2 = 5e-3
 MAX_ABS = 2e-2
-N_SAMPLE = 96
+N_SAMPLE = 512
+
+# bf16 output: raw max-abs <= 2e-2 where the outputs stay small against bf16's spacing (tensor-parallel
+# partial sums, Qwen-sized layers); unsharded and expert-parallel Mixtral-sized outputs reach |y| >= 8,
+# where the format's own spacing is 2^-4, and are gated on the error beyond half an ulp of the reference
+RAW_BF16_GATE = lambda key: not key.startswith("mixtral") or key == "mixtral_tp4"
 
 CASES = [("mixtral", 16), ("mixtral", 4096), ("mixtral_tp4", 64), ("mixtral_tp4", 8192),
          ("mixtral_ep4_hot", 8192), ("mixtral_ep4_cold", 8192), ("qwen", 32), ("qwen", 4096),
@@ -101,8 +108,8 @@ def test_full_size_against_oracle(key, T):
         assert R < 0.15 * T * k
 
     # ---- floating point, on a token sample (GPU routing decisions, oracle arithmetic)
-    rng = np.random.default_rng(1)
-    sel = np.sort(rng.choice(T, size=min(T, N_SAMPLE), replace=False))
+    sel, n_edge, n_sliced = stratified_tokens(T, k, offs, row_src, layer.ffn_shard, N_SAMPLE)
+    print("  sample: %d tokens (%d edge rows, %d of them in K-sliced tiles)" % (sel.size, n_edge, n_sliced), flush=True)
     shared = (li.ws_gate, li.ws_up, li.ws_down) if li.ws_gate is not None else None
     ref = O.expert_layer(li.x[sel], None, k, shape.renorm, shape.n_local_experts, shape.expert_offset, li.w_gate,
                          li.w_up, li.w_down, shared=shared, w_shared_gate=li.w_shared_gate if shared else None,
@@ -117,3 +124,5 @@ def test_full_size_against_oracle(key, T):
     assert np.abs(d32).max() < MAX_ABS
     # bf16 output: the format's own spacing reaches 2^-4 at |y| >= 8, so allow half an ulp on top
     assert np.max(np.abs(dbf) - 0.5 * _ulp_bf16(ref)) < MAX_ABS
+    if RAW_BF16_GATE(key):
+        assert np.abs(dbf).max() < MAX_ABS
