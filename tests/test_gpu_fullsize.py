@@ -19,10 +19,11 @@ REL_L2 = 5e-3
 MAX_ABS = 2e-2
 N_SAMPLE = 512
 
-# bf16 output: raw max-abs <= 2e-2 where the outputs stay small against bf16's spacing (tensor-parallel
-# partial sums, Qwen-sized layers); unsharded and expert-parallel Mixtral-sized outputs reach |y| >= 8,
-# where the format's own spacing is 2^-4, and are gated on the error beyond half an ulp of the reference
-RAW_BF16_GATE = lambda key: not key.startswith("mixtral") or key == "mixtral_tp4"
+# bf16 output: raw max-abs <= 2e-2 where the outputs stay small against bf16's spacing (Mixtral's
+# tensor-parallel partial sums, |y| < 5; the Qwen1.5-sized layer, |y| < 3).  Unsharded and
+# expert-parallel Mixtral-sized outputs and Qwen2-57B's reach |y| >= 8, where the format's own
+# spacing is 2^-4: those are gated on the error beyond half an ulp of the reference.
+RAW_BF16_GATE = lambda key: key in ("mixtral_tp4", "qwen", "qwen_tp4_ep2")
 
 CASES = [("mixtral", 16), ("mixtral", 4096), ("mixtral_tp4", 64), ("mixtral_tp4", 8192),
          ("mixtral_ep4_hot", 8192), ("mixtral_ep4_cold", 8192), ("qwen", 32), ("qwen", 4096),
