@@ -114,6 +114,24 @@ int moe_permute(const void* x_bf16, const int32_t* topk_idx, int32_t T, int32_t 
                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * moe_permute for callers that cannot allocate device memory or bring a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus
+ * the workspace), same results bit for bit; the per-workgroup expert counts of the large-batch
+ * path live in a static device array of the library (MOE_PERMUTE_STATIC_MAX_COUNTS int32 = 1 MiB
+ * per GPU, held until the process ends).  The call allocates nothing and frees nothing.
+ * Limit: ceil(T*k / 1024) * n_local_experts <= MOE_PERMUTE_STATIC_MAX_COUNTS when T*k > 2048 (smaller
+ * batches use no scratch); beyond it the call returns MOE_ERR_WORKSPACE and enqueues nothing.
+ * The array's device address is resolved on the first call on each device (a host-side lookup,
+ * no stream work): make that first call outside a graph capture.  All calls on one GPU share the
+ * array: calls that overlap there (different streams, or graphs replayed concurrently) race and
+ * must be serialised by the caller.  Nothing in it has to start at zero, so no clearing is done.
+ */
+#define MOE_PERMUTE_STATIC_MAX_COUNTS 262144
+int moe_permute_static(const void* x_bf16, const int32_t* topk_idx, int32_t T, int32_t k,
+                       const moe_shard_t* shard, void* x_perm, int32_t* expert_offsets,
+                       int32_t* row_src, int32_t* slot_row, void* stream);
+
+/*
  * Expert networks on the permuted rows (grouped SwiGLU FFN, bf16 MFMA, fp32 accumulate).
  * For the rows r in [expert_offsets[e], expert_offsets[e+1]) of local expert e:
  *   g = x_r Wg_e^T, u = x_r Wu_e^T, h = silu(g) * u (rounded once to bf16), y_r = h Wd_e^T.

@@ -26,8 +26,9 @@ MOE_FFN_TILED = 1 << 6
 MOE_FFN_LEAVE_ROOM = 1 << 7
 MOE_MAX_EXPERTS = 256
 MOE_MAX_TOPK = 16
+MOE_PERMUTE_STATIC_MAX_COUNTS = 262144
 
-EXPORTS = ("moe_route_topk", "moe_permute", "moe_expert_ffn", "moe_expert_ffn_gather", "moe_combine", "moe_workspace_bytes",
+EXPORTS = ("moe_route_topk", "moe_permute", "moe_permute_static", "moe_expert_ffn", "moe_expert_ffn_gather", "moe_combine", "moe_workspace_bytes",
            "moe_ffn_workspace_bytes", "moe_status_string")
 DEBUG_EXPORTS = ("moe_debug_gemm_units", "moe_debug_ffn_plan", "moe_debug_down_slices", "moe_debug_device_units")
 INT4_EXPORTS = ("moe_int4_dequantize", "moe_int4_quantize")
@@ -62,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.moe_route_topk.restype = ctypes.c_int
         L.moe_permute.argtypes = [vp, vp, i32, i32, shp, vp, vp, vp, vp, vp, sz, vp]
         L.moe_permute.restype = ctypes.c_int
+        L.moe_permute_static.argtypes = [vp, vp, i32, i32, shp, vp, vp, vp, vp, vp]
+        L.moe_permute_static.restype = ctypes.c_int
         L.moe_expert_ffn.argtypes = [vp, vp, i32, shp, vp, vp, vp, vp, vp, vp, sz, u32, vp]
         L.moe_expert_ffn.restype = ctypes.c_int
         L.moe_expert_ffn_gather.argtypes = [vp, vp, i32, vp, i32, shp, vp, vp, vp, vp, vp, vp, sz, u32, vp]
@@ -138,6 +141,12 @@ def moe_permute(x, topk_idx, T, k, shard: MoeShard, x_perm, expert_offsets, row_
     _check("moe_permute", lib().moe_permute(_ptr(x), _ptr(topk_idx), T, k, ctypes.byref(shard), _ptr(x_perm),
                                             _ptr(expert_offsets), _ptr(row_src), _ptr(slot_row), _ptr(workspace),
                                             workspace_bytes, _stream(stream)))
+
+
+def moe_permute_static(x, topk_idx, T, k, shard: MoeShard, x_perm, expert_offsets, row_src, slot_row, stream=None):
+    _check("moe_permute_static", lib().moe_permute_static(_ptr(x), _ptr(topk_idx), T, k, ctypes.byref(shard),
+                                                          _ptr(x_perm), _ptr(expert_offsets), _ptr(row_src),
+                                                          _ptr(slot_row), _stream(stream)))
 
 
 def moe_ffn_workspace_bytes(cap_rows, shard: MoeShard) -> int:

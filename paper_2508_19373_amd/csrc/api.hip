@@ -75,6 +75,24 @@ int moe_permute(const void* x_bf16, const int32_t* topk_idx, int32_t T, int32_t 
                                         static_cast<hipStream_t>(stream)));
 }
 
+int moe_permute_static(const void* x_bf16, const int32_t* topk_idx, int32_t T, int32_t k, const moe_shard_t* shard,
+                       void* x_perm, int32_t* expert_offsets, int32_t* row_src, int32_t* slot_row, void* stream) {
+  const int st = shard_status(shard);
+  if (st != MOE_OK) return st;
+  if (T < 0 || k < 1 || k > MOE_MAX_TOPK || k > shard->n_experts) return MOE_ERR_INVALID_ARG;
+  if ((int64_t)T * k >= (1 << 24)) return MOE_ERR_INVALID_ARG;
+  if (topk_idx == nullptr || expert_offsets == nullptr || row_src == nullptr || slot_row == nullptr)
+    return MOE_ERR_INVALID_ARG;
+  if (x_perm != nullptr && x_bf16 == nullptr) return MOE_ERR_INVALID_ARG;
+  if (shard->hidden % 8 != 0) return MOE_ERR_UNSUPPORTED_SHAPE;
+  if (!aligned16(x_bf16) || !aligned16(x_perm)) return MOE_ERR_INVALID_ARG;
+  if (moe::permute_static_counts(T, k, shard->n_local_experts) > MOE_PERMUTE_STATIC_MAX_COUNTS)
+    return MOE_ERR_WORKSPACE;  // beyond the static scratch: use moe_permute with a caller workspace
+  return hip_status(moe::launch_permute_static(x_bf16, topk_idx, T, k, shard->hidden, shard->n_local_experts,
+                                               shard->expert_offset, x_perm, expert_offsets, row_src, slot_row,
+                                               static_cast<hipStream_t>(stream)));
+}
+
 static int expert_ffn_common(const void* x, moe::RowMap rows, const int32_t* expert_offsets, int32_t cap_rows,
                              const moe_shard_t* shard, const void* w_gate, const void* w_up, const void* w_down,
                              void* h_workspace, void* y_perm, void* workspace, size_t workspace_bytes, uint32_t flags,

@@ -49,6 +49,11 @@ hipError_t launch_permute(const void* x, const int32_t* topk_idx, int T, int k, 
                           void* x_perm, int32_t* expert_offsets, int32_t* row_src, int32_t* slot_row,
                           void* workspace, hipStream_t stream);
 size_t permute_workspace_bytes(int T, int k, int n_local);
+// The same with the library's own static scratch; permute_static_counts: int32 counts it would use.
+hipError_t launch_permute_static(const void* x, const int32_t* topk_idx, int T, int k, int H, int n_local, int offset,
+                                 void* x_perm, int32_t* expert_offsets, int32_t* row_src, int32_t* slot_row,
+                                 hipStream_t stream);
+size_t permute_static_counts(int T, int k, int n_local);
 // est_rows: the rows this shard expects (cap_rows scaled by its share of the experts); it steers the
 // choice of kernels and K slices only, every bound is taken from cap_rows.
 hipError_t launch_expert_ffn(const void* x_perm, RowMap rows, const int32_t* expert_offsets, int cap_rows, int est_rows,

@@ -10,8 +10,39 @@
 // Gather kernel: coalesced 16-byte-per-lane row copies x[row_src[r] / k] -> x_perm[r].
 #include "moe_internal.hpp"
 
+#include <mutex>
+
 namespace moe {
 namespace {
+
+// Scratch of moe_permute_static: the per-workgroup expert counts of the large-batch path, in device
+// memory that belongs to the library (each GPU the library runs on holds its own copy until the
+// process ends).  The name below is a host-side handle only; host code uses the address that
+// static_scratch() resolves per device.
+constexpr size_t kStaticScratchInts = MOE_PERMUTE_STATIC_MAX_COUNTS;  // 1 MiB
+static __device__ __align__(256) int32_t scratch[kStaticScratchInts];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+int32_t* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, resolved once per device.
+hipError_t static_scratch(int32_t** out) {
+  int dev = -1;
+  hipError_t err = hipGetDevice(&dev);
+  if (err != hipSuccess) return err;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (err != hipSuccess) return err;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = static_cast<int32_t*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
 
 constexpr int kIdxThreads = 1024;
 constexpr int kIdxWaves = kIdxThreads / kWave;
@@ -217,6 +248,23 @@ __global__ __launch_bounds__(kGatherThreads) void gather_rows_kernel(const uint4
 size_t permute_workspace_bytes(int T, int k, int n_local) {
   const size_t blocks = ((size_t)T * k + kIdxThreads - 1) / kIdxThreads;
   return 256 + blocks * n_local * sizeof(int32_t);
+}
+
+size_t permute_static_counts(int T, int k, int n_local) {
+  const size_t A = (size_t)T * k;
+  if (A <= 2 * kIdxThreads) return 0;  // the one-workgroup path keeps its counts in LDS
+  return (A + kIdxThreads - 1) / kIdxThreads * n_local;
+}
+
+hipError_t launch_permute_static(const void* x, const int32_t* topk_idx, int T, int k, int H, int n_local, int offset,
+                                 void* x_perm, int32_t* expert_offsets, int32_t* row_src, int32_t* slot_row,
+                                 hipStream_t stream) {
+  int32_t* ptr = nullptr;
+  const hipError_t err = static_scratch(&ptr);
+  if (err != hipSuccess) return err;
+  // every count the scan and place kernels read was written by the rank kernel of the same call:
+  // nothing has to start at zero, whatever the last call left behind
+  return launch_permute(x, topk_idx, T, k, H, n_local, offset, x_perm, expert_offsets, row_src, slot_row, ptr, stream);
 }
 
 hipError_t launch_permute(const void* x, const int32_t* topk_idx, int T, int k, int H, int n_local, int offset,
