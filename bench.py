@@ -172,11 +172,11 @@ def main():
                                                       layer.expert_offsets, layer.row_src, layer.slot_row,
                                                       layer.workspace), it, torch)
     if gather:   # the routed experts read their rows of x in place
-        ffn = lambda fl: B.moe_expert_ffn_gather(x, layer.row_src, k, layer.expert_offsets, T * k, layer.shard,
+        ffn = lambda fl: B.moe_expert_ffn_gather(x, layer.row_src, k, layer.expert_offsets, T * k, layer.ffn_shard,
                                                  layer.w_gate, layer.w_up, layer.w_down, layer.h_ws, layer.y_perm,
                                                  layer.ffn_ws, fl)
     else:
-        ffn = lambda fl: B.moe_expert_ffn(layer.x_perm, layer.expert_offsets, T * k, layer.shard, layer.w_gate,
+        ffn = lambda fl: B.moe_expert_ffn(layer.x_perm, layer.expert_offsets, T * k, layer.ffn_shard, layer.w_gate,
                                           layer.w_up, layer.w_down, layer.h_ws, layer.y_perm, layer.ffn_ws, fl)
     br["ffn_gateup_swiglu"] = time_events(lambda: ffn(B.MOE_FFN_SKIP_DOWN), it, torch)
     br["ffn_down"] = time_events(lambda: ffn(B.MOE_FFN_SKIP_GATEUP), it, torch)

@@ -38,10 +38,8 @@ def features_of(row) -> np.ndarray:
                 inter_shared_slice=row["inter_shared"] / tp)
     # derived from the same parameters: expected rows per local expert (decides the regime), the
     # module's FLOPs and the bytes of weights it touches (their ratio is the arithmetic intensity)
-    n_loc = vals["n_local_experts"]
     vals["rows_per_expert"] = row["tokens"] * row["top_k"] / row["n_experts"]
     vals["flops"] = module_flops(row)
-    active = n_loc * (1.0 - (1.0 - row["top_k"] / row["n_experts"]) ** row["tokens"])
     vals["weight_bytes"] = weight_bytes(row)
     return np.log2(np.maximum(np.array([vals[k] for k in FEATURES], dtype=np.float64), 1.0))
 

@@ -107,11 +107,25 @@ class ExpertShardLayer:
         self.overlap_shared = bool(overlap_shared) and shared is not None
         self._side = _side_stream(device) if self.overlap_shared else None
         self.Tmax = -1
+        # {0, T} for the shared expert's call, one immutable device tensor per token count: a
+        # captured graph keeps reading the tensor it was captured with
+        self._sh_offsets = {}
+        # buffers a captured graph still points at are kept alive when a larger batch makes the
+        # layer allocate anew, so replaying an older graph stays valid (it works on its own buffers)
+        self._captured, self._retired = False, []
         if max_tokens:
             self._alloc(max_tokens)
 
+    _BUFFERS = ("logits", "topk_idx", "topk_w", "x_perm", "expert_offsets", "row_src", "slot_row", "h_ws", "y_perm",
+                "workspace", "ffn_ws", "y_out", "h_sh", "y_shared", "ffn_ws_sh")
+
+    def _retire(self, names):
+        if self._captured:
+            self._retired.extend(getattr(self, n) for n in names if getattr(self, n, None) is not None)
+
     def _alloc(self, T):
         d, k, H, E = self.device, self.k, self.H, self.E
+        self._retire(self._BUFFERS)
         cap = max(T * k, 1)
         Tn = max(T, 1)
         ydt = torch.bfloat16 if self.y_perm_bf16 else torch.float32
@@ -128,12 +142,28 @@ class ExpertShardLayer:
         self.ffn_ws = torch.empty(max(B.moe_ffn_workspace_bytes(cap, self.ffn_shard), 256), dtype=torch.uint8, device=d)
         self.y_out = torch.empty((Tn, H), dtype=torch.float32 if self.out_f32 else torch.bfloat16, device=d)
         if self.shared is not None:
-            self.sh_offsets = torch.zeros(2, dtype=torch.int32, device=d)
             self.h_sh = torch.empty((Tn, self.shared_shard.inter_slice), dtype=torch.bfloat16, device=d)
             self.y_shared = torch.empty((Tn, H), dtype=ydt, device=d)
             self.ffn_ws_sh = torch.empty(max(B.moe_ffn_workspace_bytes(Tn, self.shared_shard), 256),
                                          dtype=torch.uint8, device=d)
         self.Tmax = T
+
+    def _shared_offsets(self, T):
+        """Device tensor {0, T}: written once, on first use of this token count, and complete
+        before this returns (whatever stream the kernels then run on)."""
+        t = self._sh_offsets.get(T)
+        if t is None:
+            if torch.cuda.is_current_stream_capturing():
+                raise RuntimeError("run one eager forward with this token count before capturing a graph")
+            t = torch.tensor([0, T], dtype=torch.int32).to(self.device)
+            torch.cuda.current_stream().synchronize()
+            self._sh_offsets[T] = t
+        return t
+
+    @property
+    def sh_offsets(self):
+        """The shared expert's offsets for the most recent token count."""
+        return self._sh_offsets[self._last_T]
 
     def gathers(self, T) -> bool:
         """Whether a forward of T tokens reads the routed experts' rows of x in place (no permuted copy)."""
@@ -144,15 +174,20 @@ class ExpertShardLayer:
     def forward(self, x: torch.Tensor, logits: torch.Tensor | None = None, stream=None) -> torch.Tensor:
         T = x.shape[0]
         if T > self.Tmax:
+            if torch.cuda.is_current_stream_capturing():
+                raise RuntimeError("run one eager forward with this token count before capturing a graph")
             self._alloc(T)
+        self._last_T = T
         k, H, E = self.k, self.H, self.E
         # the FFN scratch depends on the regime (decode-sized calls need split-K partials)
         need = B.moe_ffn_workspace_bytes(T * k, self.ffn_shard)
         if need > self.ffn_ws.numel():
+            self._retire(("ffn_ws",))
             self.ffn_ws = torch.empty(need, dtype=torch.uint8, device=self.device)
         if self.shared is not None:
             need = B.moe_ffn_workspace_bytes(T, self.shared_shard)
             if need > self.ffn_ws_sh.numel():
+                self._retire(("ffn_ws_sh",))
                 self.ffn_ws_sh = torch.empty(need, dtype=torch.uint8, device=self.device)
         flags = B.MOE_RENORM_TOPK if self.renorm else 0
         if logits is not None:
@@ -164,11 +199,7 @@ class ExpertShardLayer:
             rflag |= routed_hint_beside_shared(self.ffn_shard, self.shared_shard, T)
         y_shared, joined = None, None
         if self.shared is not None:
-            if getattr(self, "_sh_T", None) != T:
-                if torch.cuda.is_current_stream_capturing():
-                    raise RuntimeError("run one eager forward with this token count before capturing a graph")
-                self.sh_offsets.copy_(torch.tensor([0, T], dtype=torch.int32))
-                self._sh_T = T
+            sh_offsets = self._shared_offsets(T)
             y_shared = self.y_shared
         if self.shared is not None and self.overlap_shared:
             if stream is not None:
@@ -178,7 +209,7 @@ class ExpertShardLayer:
             # a streaming shared expert leaves 16 compute units free, so that the router and the
             # permutation on the main stream, each a workgroup or two on the critical path, start
             # at once instead of waiting for a resident workgroup to finish (-2 to -3.5 % at 16 to 64 tokens)
-            B.moe_expert_ffn(x, self.sh_offsets, T, self.shared_shard, self.shared[0], self.shared[1], self.shared[2],
+            B.moe_expert_ffn(x, sh_offsets, T, self.shared_shard, self.shared[0], self.shared[1], self.shared[2],
                              self.h_sh, self.y_shared, self.ffn_ws_sh, yflag | B.MOE_FFN_LEAVE_ROOM, self._side)
             joined = self._side
         B.moe_route_topk(x, self.w_router, self.logits, T, H, E, k, flags, self.topk_idx, self.topk_w, stream)
@@ -192,7 +223,7 @@ class ExpertShardLayer:
             B.moe_expert_ffn(self.x_perm, self.expert_offsets, T * k, self.ffn_shard, self.w_gate, self.w_up,
                              self.w_down, self.h_ws, self.y_perm, self.ffn_ws, rflag, stream)
         if self.shared is not None and not self.overlap_shared:
-            B.moe_expert_ffn(x, self.sh_offsets, T, self.shared_shard, self.shared[0], self.shared[1], self.shared[2],
+            B.moe_expert_ffn(x, sh_offsets, T, self.shared_shard, self.shared[0], self.shared[1], self.shared[2],
                              self.h_sh, self.y_shared, self.ffn_ws_sh, yflag, stream)
         if joined is not None:
             torch.cuda.current_stream().wait_stream(joined)
@@ -212,6 +243,7 @@ class ExpertShardLayer:
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         graph = torch.cuda.CUDAGraph()
+        self._captured = True
         with torch.cuda.stream(side):
             with torch.cuda.graph(graph, stream=side):
                 out = self.forward(x, logits)

@@ -508,6 +508,42 @@ def test_layer_qwen_like_with_shared_expert(T, overlap):
         torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("overlap", [True, False])
+def test_captured_graph_survives_other_token_counts_and_reallocation(overlap):
+    # a graph captured at 16 tokens keeps its own {0, T} offsets and its own buffers: an eager call
+    # with more tokens in between, and one that makes the layer allocate larger buffers, must not
+    # change what a replay computes
+    li16 = I.make_layer_inputs(SMALL_QWEN, 16, 0)
+    li48 = I.make_layer_inputs(SMALL_QWEN, 48, 1)
+    li200 = I.make_layer_inputs(SMALL_QWEN, 200, 2)
+    layer = ExpertShardLayer.from_inputs(li16, overlap_shared=overlap, max_tokens=64)
+    x16, x48, x200 = bf16_tensor(li16.x), bf16_tensor(li48.x), bf16_tensor(li200.x)
+    first = layer.forward(x16).clone()
+    graph, out = layer.capture(x16)
+    y48 = layer.forward(x48).clone()           # same buffers, other token count
+    out.zero_()
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out, first)
+    y200 = layer.forward(x200).clone()         # beyond max_tokens: the layer allocates anew
+    filler = torch.full((1 << 22,), 1.0, device="cuda")   # anything the allocator hands out now must not be the graph's
+    out.zero_()
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out, first)
+    assert torch.equal(layer.forward(x48), y48) and torch.equal(layer.forward(x200), y200)
+    ref = _oracle_layer(li200, layer.logits[:200].cpu().numpy())
+    assert _rel(y200.float().cpu().numpy().astype(np.float64), ref) < REL_L2
+    del filler
+    # an explicit stream, shared expert on that same stream
+    if not overlap:
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        y = layer.forward(x16, stream=s)
+        s.synchronize()
+        assert torch.equal(y, first)
+
+
 def test_layer_hybrid_ep_tp_shard():
     T = 200
     s = SMALL_TP.shard(tp_degree=2, tp_rank=1, ep_degree=2, ep_rank=1)
