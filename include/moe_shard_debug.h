@@ -41,6 +41,23 @@ int32_t moe_debug_gemm_units(const int32_t* expert_offsets, int32_t n_local, int
  */
 int32_t moe_debug_ffn_plan(int32_t cap_rows, const moe_shard_t* shard, int32_t* plan);
 
+/*
+ * Row-block height of the tiled kernels moe_expert_ffn would use for (cap_rows, shard): 256 (row
+ * blocks of 256 rows plus 128- and 64-row remainder tiles, moe_debug_gemm_units), or 160 (every
+ * expert's rows in blocks of 160, moe_debug_even_units), which the library picks for calls with a
+ * few hundred rows per expert: there a remainder tile behind one 256-row tile would stream the
+ * expert's weights from HBM a second time ("Generative Inference": such launches are bound by
+ * loading weights, not by compute).  Returns the height or a negative MOE_ERR_* code.
+ */
+int32_t moe_debug_tile_rows(int32_t cap_rows, const moe_shard_t* shard);
+
+/*
+ * The work list of the 160-row tiling, in the record format of moe_debug_gemm_units (tile height
+ * 160 or 0).  Arguments and return value as there.
+ */
+int32_t moe_debug_even_units(const int32_t* expert_offsets, int32_t n_local, int32_t cap_rows,
+                             int32_t n_col_blocks, int32_t* units, int32_t max_units);
+
 #define MOE_DEBUG_SLICE_INTS 8
 
 /*
@@ -69,7 +86,7 @@ int32_t moe_debug_down_slices(const int32_t* expert_offsets, int32_t cap_rows, c
  * GEMM kernels use (one wavefront per workgroup id), for tests that compare it with the host code.
  * expert_offsets [n_local+1] int32 DEVICE; n_col_blocks, nk (k-tiles of 64): as the kernel is launched
  * max_slices     0: the plain list of moe_debug_gemm_units; >= 1: the sliced list of
- *                moe_debug_down_slices with that maximum
+ *                moe_debug_down_slices with that maximum; -1: the list of moe_debug_even_units
  * units          [max_units][MOE_DEBUG_DEVICE_INTS] int32 DEVICE, written asynchronously on `stream`:
  *                {tile height (0 = no work), local expert, row0, row_end, column block, slice,
  *                 first k-tile, k-tiles, scratch row of row0 (-1: writes y_perm)}

@@ -30,7 +30,8 @@ MOE_PERMUTE_STATIC_MAX_COUNTS = 262144
 
 EXPORTS = ("moe_route_topk", "moe_permute", "moe_permute_static", "moe_expert_ffn", "moe_expert_ffn_gather", "moe_combine", "moe_workspace_bytes",
            "moe_ffn_workspace_bytes", "moe_status_string")
-DEBUG_EXPORTS = ("moe_debug_gemm_units", "moe_debug_ffn_plan", "moe_debug_down_slices", "moe_debug_device_units")
+DEBUG_EXPORTS = ("moe_debug_gemm_units", "moe_debug_ffn_plan", "moe_debug_down_slices", "moe_debug_device_units",
+                 "moe_debug_tile_rows", "moe_debug_even_units")
 INT4_EXPORTS = ("moe_int4_dequantize", "moe_int4_quantize")
 INT4_GROUP = 64
 DEBUG_UNIT_INTS = 5
@@ -89,6 +90,10 @@ def lib() -> ctypes.CDLL:
         L.moe_debug_device_units.restype = i32
         L.moe_debug_gemm_units.argtypes = [vp, i32, i32, i32, vp, i32]
         L.moe_debug_gemm_units.restype = i32
+        L.moe_debug_even_units.argtypes = [vp, i32, i32, i32, vp, i32]
+        L.moe_debug_even_units.restype = i32
+        L.moe_debug_tile_rows.argtypes = [i32, shp]
+        L.moe_debug_tile_rows.restype = i32
         _lib = L
     return _lib
 
@@ -198,6 +203,27 @@ def moe_debug_gemm_units(expert_offsets, cap_rows, n_col_blocks):
     if n < 0:
         raise MoeError("moe_debug_gemm_units", n)
     return out[:n]
+
+
+def moe_debug_even_units(expert_offsets, cap_rows, n_col_blocks):
+    """Host-only: the work list of the 160-row tiling for one routing, records as moe_debug_gemm_units."""
+    import numpy as np
+    offs = np.ascontiguousarray(expert_offsets, dtype=np.int32)
+    n_local = offs.size - 1
+    max_units = 8 * (((cap_rows // 160 + n_local) * n_col_blocks + 7) // 8)
+    out = np.zeros((max(max_units, 1), DEBUG_UNIT_INTS), dtype=np.int32)
+    n = lib().moe_debug_even_units(offs.ctypes.data, n_local, cap_rows, n_col_blocks, out.ctypes.data, max_units)
+    if n < 0:
+        raise MoeError("moe_debug_even_units", n)
+    return out[:n]
+
+
+def moe_debug_tile_rows(cap_rows, shard: MoeShard) -> int:
+    """Host-only: row-block height (256 or 160) of the tiled kernels moe_expert_ffn would use."""
+    n = lib().moe_debug_tile_rows(cap_rows, ctypes.byref(shard))
+    if n < 0:
+        raise MoeError("moe_debug_tile_rows", n)
+    return int(n)
 
 
 def moe_debug_down_slices(expert_offsets, cap_rows, shard: MoeShard, with_units=False):

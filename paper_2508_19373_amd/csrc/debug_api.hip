@@ -3,6 +3,7 @@
 // routing is covered exactly once.
 #include "moe_shard_debug.h"
 #include "moe_internal.hpp"
+#include "unit_list_even.hpp"
 #include "unit_list_wave.hpp"
 
 extern "C" int32_t moe_debug_gemm_units(const int32_t* expert_offsets, int32_t n_local, int32_t cap_rows,
@@ -40,6 +41,41 @@ extern "C" int32_t moe_debug_ffn_plan(int32_t cap_rows, const moe_shard_t* shard
   moe::ffn_plan(cap_rows, moe::expected_rows(cap_rows, shard), shard->n_local_experts, shard->hidden,
                 shard->inter_slice, plan);
   return MOE_OK;
+}
+
+extern "C" int32_t moe_debug_tile_rows(int32_t cap_rows, const moe_shard_t* shard) {
+  if (cap_rows < 0 || shard == nullptr) return MOE_ERR_INVALID_ARG;
+  if (shard->n_experts < 1 || shard->n_local_experts < 1 || shard->n_local_experts > shard->n_experts ||
+      shard->hidden < 64 || shard->inter_slice < 64)
+    return MOE_ERR_INVALID_ARG;
+  return moe::tiled_block_rows(cap_rows, moe::expected_rows(cap_rows, shard), shard->n_local_experts, shard->hidden,
+                               shard->inter_slice);
+}
+
+extern "C" int32_t moe_debug_even_units(const int32_t* expert_offsets, int32_t n_local, int32_t cap_rows,
+                                        int32_t n_col_blocks, int32_t* units, int32_t max_units) {
+  using namespace moe::gg;
+  if (expert_offsets == nullptr || units == nullptr || n_local < 1 || cap_rows < 0 || n_col_blocks < 1)
+    return MOE_ERR_INVALID_ARG;
+  for (int e = 0; e < n_local; ++e)
+    if (expert_offsets[e] > expert_offsets[e + 1]) return MOE_ERR_INVALID_ARG;
+  if (expert_offsets[0] < 0 || expert_offsets[n_local] > cap_rows) return MOE_ERR_INVALID_ARG;
+  const int grid = even_max_ids(cap_rows, n_local, n_col_blocks);
+  if (grid > max_units) return MOE_ERR_WORKSPACE;
+  const int n_tiles = even_tiles(expert_offsets, n_local, n_col_blocks);
+  for (int b = 0; b < grid; ++b) {
+    int32_t* rec = units + (size_t)b * MOE_DEBUG_UNIT_INTS;
+    for (int i = 0; i < MOE_DEBUG_UNIT_INTS; ++i) rec[i] = 0;
+    const int idx = even_tile_index(n_tiles, b);
+    if (idx < 0) continue;
+    const TileCoord tc = even_locate(expert_offsets, n_local, n_col_blocks, idx);
+    rec[0] = kEvenRows;
+    rec[1] = tc.expert;
+    rec[2] = tc.row0;
+    rec[3] = tc.row_end;
+    rec[4] = tc.nb;
+  }
+  return grid;
 }
 
 extern "C" int32_t moe_debug_down_slices(const int32_t* expert_offsets, int32_t cap_rows, const moe_shard_t* shard,
@@ -94,7 +130,18 @@ __global__ __launch_bounds__(64) void device_units_kernel(const int32_t* __restr
                                                          int32_t* __restrict__ units) {
   using namespace moe::gg;
   int32_t rec[MOE_DEBUG_DEVICE_INTS] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
-  if (max_slices == 0) {
+  if (max_slices < 0) {
+    TileCoord tc;
+    if (even_find_tile(expert_offsets, n_local, n_col_blocks, blockIdx.x, tc)) {
+      rec[0] = kEvenRows;
+      rec[1] = tc.expert;
+      rec[2] = tc.row0;
+      rec[3] = tc.row_end;
+      rec[4] = tc.nb;
+      rec[7] = nk;
+      rec[8] = -1;
+    }
+  } else if (max_slices == 0) {
     int cls = 0;
     TileCoord tc;
     if (find_tile(expert_offsets, n_local, n_col_blocks, blockIdx.x, cls, tc)) {
@@ -130,9 +177,11 @@ extern "C" int32_t moe_debug_device_units(const int32_t* expert_offsets, int32_t
                                           int32_t max_units, void* stream) {
   using namespace moe::gg;
   if (expert_offsets == nullptr || units == nullptr || n_local < 1 || n_local > MOE_MAX_EXPERTS || cap_rows < 0 ||
-      n_col_blocks < 1 || nk < 1 || max_slices < 0 || max_slices > 16)
+      n_col_blocks < 1 || nk < 1 || max_slices < -1 || max_slices > 16)
     return MOE_ERR_INVALID_ARG;
-  const int grid = max_slices > 0 ? sliced_grid(cap_rows, n_local, n_col_blocks) : max_grid(cap_rows, n_local, n_col_blocks);
+  const int grid = max_slices < 0 ? even_max_ids(cap_rows, n_local, n_col_blocks)
+                                  : (max_slices > 0 ? sliced_grid(cap_rows, n_local, n_col_blocks)
+                                                    : max_grid(cap_rows, n_local, n_col_blocks));
   if (grid > max_units) return MOE_ERR_WORKSPACE;
   hipLaunchKernelGGL(device_units_kernel, dim3(grid), dim3(64), 0, static_cast<hipStream_t>(stream), expert_offsets,
                      n_local, n_col_blocks, nk, max_slices, units);

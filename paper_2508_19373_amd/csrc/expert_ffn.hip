@@ -70,6 +70,35 @@ hipError_t launch_pair_dlds(const void* x_perm, RowMap rows, const int32_t* expe
   return hipGetLastError();
 }
 
+// A few hundred rows per expert: tiles of 160 rows from the one-height work list (unit_list_even.hpp).
+hipError_t launch_pair_even(const void* x_perm, RowMap rows, const int32_t* expert_offsets, int cap_rows, int n_local,
+                            int H, int I_s, const void* w_gate, const void* w_up, const void* w_down, void* h_ws,
+                            void* y_perm, uint32_t flags, hipStream_t stream) {
+  const dim3 block(256);
+  uint16_t* hw = static_cast<uint16_t*>(h_ws);
+  if (!(flags & MOE_FFN_SKIP_GATEUP)) {
+    const int ncb = (I_s + 127) / 128;
+    hipLaunchKernelGGL((gg::grouped_gemm_even_kernel<256, true, uint16_t>),
+                       dim3((unsigned)gg::even_max_ids(cap_rows, n_local, ncb)), block, 0, stream,
+                       static_cast<const uint16_t*>(x_perm), expert_offsets, n_local, cap_rows,
+                       static_cast<const uint16_t*>(w_gate), static_cast<const uint16_t*>(w_up), I_s, H, hw, ncb, rows);
+    const hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+  }
+  if (flags & MOE_FFN_SKIP_DOWN) return hipSuccess;
+  const int ncb = (H + 255) / 256;
+  const dim3 grid((unsigned)gg::even_max_ids(cap_rows, n_local, ncb));
+  if (flags & MOE_Y_PERM_BF16)
+    hipLaunchKernelGGL((gg::grouped_gemm_even_kernel<256, false, uint16_t>), grid, block, 0, stream, hw, expert_offsets,
+                       n_local, cap_rows, static_cast<const uint16_t*>(w_down), static_cast<const uint16_t*>(nullptr), H,
+                       I_s, static_cast<uint16_t*>(y_perm), ncb, RowMap{nullptr, 1});
+  else
+    hipLaunchKernelGGL((gg::grouped_gemm_even_kernel<256, false, float>), grid, block, 0, stream, hw, expert_offsets,
+                       n_local, cap_rows, static_cast<const uint16_t*>(w_down), static_cast<const uint16_t*>(nullptr), H,
+                       I_s, static_cast<float*>(y_perm), ncb, RowMap{nullptr, 1});
+  return hipGetLastError();
+}
+
 // Decode-sized groups, register-resident activations (grouped_walk.hpp).  Returns false when the
 // K extent is not one of the instantiated (wavefronts x steps) splits.
 constexpr int kWalkSlots = 512;  // 8-wavefront workgroups resident at once with MT = 1 (2 per CU); half of it
@@ -206,7 +235,25 @@ inline bool prefer_walk(int cap_rows, int est_rows, int n_local, int n_out, int 
   return walk < tiled;
 }
 
+// Row-block height of the tiled kernels for a call: 160 (the one-height list) where the 256-row
+// tiling would give most experts a remainder tile that streams their weights a second time and the
+// launch has enough tiles for that to be what bounds it, else 256.
+#ifndef MOE_EVEN_MODE
+#define MOE_EVEN_MODE 0  // 1: always 160, 2: never (tuning builds)
+#endif
+inline bool prefer_even(int est_rows, int n_local, int H, int I_s) {
+  if (MOE_EVEN_MODE != 0) return MOE_EVEN_MODE == 1;
+  const double avg = (double)est_rows / n_local;
+  const long tiles = (long)n_local * 2 * ((H + 255) / 256);  // down projection, two row blocks per expert
+  return avg > 225.0 && avg <= 325.0 && tiles >= 512;
+}
+
 }  // namespace
+
+int tiled_block_rows(int cap_rows, int est_rows, int n_local, int H, int I_s) {
+  (void)cap_rows;
+  return prefer_even(est_rows, n_local, H, I_s) ? gg::kEvenRows : 256;
+}
 
 size_t ffn_workspace_bytes(int cap_rows, int est_rows, int n_local, int H, int I_s) {
   if (cap_rows == 0) return 0;
@@ -242,7 +289,11 @@ hipError_t launch_expert_ffn(const void* x_perm, RowMap rows, const int32_t* exp
   if (cap_rows == 0) return hipSuccess;
   // each GEMM picks its kernel family on its own: h is row-major bf16 for both
   const int mt = decode_mt(cap_rows, est_rows, n_local);
+  const bool even = prefer_even(est_rows, n_local, H, I_s);
   auto run = [&](bool walk, uint32_t f) {
+    if (!walk && even)
+      return launch_pair_even(x_perm, rows, expert_offsets, cap_rows, n_local, H, I_s, w_gate, w_up, w_down, h_ws,
+                              y_perm, f, stream);
     if (!walk)
       return launch_pair_dlds<256>(x_perm, rows, expert_offsets, cap_rows, est_rows, n_local, H, I_s, w_gate, w_up, w_down,
                                    h_ws, y_perm, workspace, f, stream);

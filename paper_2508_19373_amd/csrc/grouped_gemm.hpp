@@ -28,6 +28,7 @@
 #include <type_traits>
 
 #include "moe_internal.hpp"
+#include "unit_list_even.hpp"
 #include "unit_list_wave.hpp"
 
 namespace moe {
@@ -194,11 +195,15 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
   // Pair order: the upper half of the row blocks row by row, the lower half column by column, so
   // operand fragments die -- and are refreshed -- at an even pace (at most 2 LDS reads per pair;
   // reading all B fragments in the last row made that row LDS-bound):
-  //   pair p < TM            : A[TM/2 + p/2][p%2] of THIS tile (lower-half A rows die at the tile's end)
+  //   pair p < TM            : A[TM/2 + p/2][p%2] of THIS tile (lower-half A rows die at the tile's end);
+  //                            these TM reads must be issued before the barrier behind pair TN - 1 (the
+  //                            stage is refilled after it), so with TM > TN they are dealt over the
+  //                            first TN pairs
   //   end of upper row i     : A[i] of the next tile
   //   end of lower column j  : B[j] of the next tile
   constexpr int HM = TM / 2, NP1 = HM * TN;
-  static_assert(TM % 2 == 0 && TN >= TM, "pair order needs an even row-block count and TN >= TM");
+  static_assert(TM % 2 == 0, "pair order needs an even row-block count");
+  constexpr int LOWER_SPAN = TM <= TN ? TM : TN;  // pairs over which the lower-half reads are dealt
   auto k_tile = [&](int kt, int sa, int sb, auto sync_tag, auto dma_a_tag, auto dma_b_tag, auto slack_tag) {
     constexpr bool SYNC = decltype(sync_tag)::value;
     constexpr bool DMA_A = decltype(dma_a_tag)::value, DMA_B = decltype(dma_b_tag)::value;
@@ -215,7 +220,11 @@ __device__ __forceinline__ void gemm_tile(uint16_t* smem, const TileCoord& tc, c
       // lane ends up with 4 CONSECUTIVE output columns of one row (one 8- or 16-byte store)
       acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[j][0], af[i][0], acc[i][j], 0, 0, 0);
       acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[j][1], af[i][1], acc[i][j], 0, 0, 0);
-      if constexpr (p < TM) read_a(sa, template_int<HM + p / 2>{}, template_int<p % 2>{});
+      if constexpr (p < LOWER_SPAN)
+        static_for<(p * TM + LOWER_SPAN - 1) / LOWER_SPAN, ((p + 1) * TM + LOWER_SPAN - 1) / LOWER_SPAN>([&](auto r_tag) {
+          constexpr int r = decltype(r_tag)::value;
+          read_a(sa, template_int<HM + r / 2>{}, template_int<r % 2>{});
+        });
       if constexpr (SYNC) {
         if constexpr (upper && j == TN - 1 && p >= TN) {  // rows 1..HM-1: after the barrier
           read_a(sa_n, template_int<i>{}, k0_);
@@ -362,6 +371,20 @@ __global__ __launch_bounds__(256) void grouped_gemm_dlds_kernel(
     gemm_tile<128, BN, 2, 2, 3, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out, rows);
   else
     gemm_tile<64, BN, 1, 4, 4, 4, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, kt0, nk, out, rows);
+}
+
+// The same GEMM on the work list of unit_list_even.hpp: every tile is 160 rows x 256 weight rows, four
+// wavefronts side by side, each with all 160 rows and 64 weight rows (10 x 4 accumulator blocks), three
+// LDS stages of each operand.  Chosen on the host for launches with a few hundred rows per expert.
+template <int BN, bool GATEUP, typename OutT>
+__global__ __launch_bounds__(256) void grouped_gemm_even_kernel(
+    const uint16_t* __restrict__ A, const int32_t* __restrict__ expert_offsets, int n_local, int cap_rows,
+    const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1, int n_out, int K, OutT* __restrict__ C,
+    int n_col_blocks, const RowMap rows) {
+  __shared__ __attribute__((aligned(1024))) uint16_t smem[kLdsBytes / 2];
+  TileCoord tc;
+  if (!even_find_tile(expert_offsets, n_local, n_col_blocks, blockIdx.x, tc)) return;
+  gemm_tile<kEvenRows, BN, 1, 4, 3, 3, GATEUP, OutT>(smem, tc, A, cap_rows, B0, B1, n_out, K, 0, K / BK, C, rows);
 }
 
 // y[r, :] += partial sums of slices 1, 2, ... in that order, for the rows the sliced kernel cut

@@ -64,6 +64,8 @@ size_t ffn_workspace_bytes(int cap_rows, int est_rows, int n_local, int H, int I
 // What launch_expert_ffn would do: {GEMM1 by the walk kernel, GEMM2 by the walk kernel, rows per
 // walk pass / 16, K slices of GEMM2}.
 void ffn_plan(int cap_rows, int est_rows, int n_local, int H, int I_s, int32_t out[4]);
+// Row-block height of the tiled kernels for such a call (256, or 160 for the one-height work list).
+int tiled_block_rows(int cap_rows, int est_rows, int n_local, int H, int I_s);
 int expected_rows(int cap_rows, const moe_shard_t* shard);
 hipError_t launch_combine(const void* y_perm, const int32_t* slot_row, const float* topk_w, int T, int k, int H,
                           const void* y_shared, const void* x, const float* w_shared_gate, void* y_out,

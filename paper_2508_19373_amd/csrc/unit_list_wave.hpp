@@ -119,7 +119,8 @@ __device__ inline WaveRouting wave_routing(const int32_t* __restrict__ expert_of
 // Tile `idx` of a list in which the lane's experts have `mbs` row blocks each, the first of them
 // `base` rows into the expert: experts in order, column blocks, row blocks fastest.
 __device__ inline TileCoord wave_locate(const WaveRouting& w, const int (&mbs)[kLaneChunks],
-                                        const int (&base)[kLaneChunks], int n_col_blocks, int idx) {
+                                        const int (&base)[kLaneChunks], int n_col_blocks, int idx,
+                                        int block_rows = 256) {
   int pre[kLaneChunks];
   wave_prefix(mbs, w.chunks, pre);
   const WaveHit h = wave_find(pre, mbs, w.chunks, idx / n_col_blocks);
@@ -130,7 +131,7 @@ __device__ inline TileCoord wave_locate(const WaveRouting& w, const int (&mbs)[k
   // (the values are uniform by construction; reading them from the first lane tells the compiler so)
   t.expert = __builtin_amdgcn_readfirstlane(h.lane + 64 * h.j);
   t.nb = __builtin_amdgcn_readfirstlane(local / m);
-  t.row0 = __builtin_amdgcn_readfirstlane(lo + wave_pick(base, h) + (local % m) * 256);
+  t.row0 = __builtin_amdgcn_readfirstlane(lo + wave_pick(base, h) + (local % m) * block_rows);
   t.row_end = __builtin_amdgcn_readfirstlane(lo + wave_pick(w.rows, h));
   return t;
 }

@@ -21,13 +21,14 @@ def edge_rows(offs, cap_rows, ffn_shard):
         if offs[e + 1] > offs[e]:
             rows.update((int(offs[e]), int(offs[e + 1]) - 1))
     H, I_s = ffn_shard.hidden, ffn_shard.inter_slice
+    even = B.moe_debug_tile_rows(cap_rows, ffn_shard) == 160
     for ncb in ((I_s + 127) // 128, (H + 255) // 256):
-        units = B.moe_debug_gemm_units(offs, cap_rows, ncb)
+        units = B.moe_debug_even_units(offs, cap_rows, ncb) if even else B.moe_debug_gemm_units(offs, cap_rows, ncb)
         for h, e, row0, row_end, nb in units[units[:, 0] > 0]:
             if nb == 0 or nb == ncb - 1:
                 rows.update((int(row0), int(min(row0 + h, row_end)) - 1))
     n_sliced = 0
-    if B.moe_ffn_workspace_bytes(cap_rows, ffn_shard) > 0:
+    if not even and B.moe_ffn_workspace_bytes(cap_rows, ffn_shard) > 0:
         _, units = B.moe_debug_down_slices(offs, cap_rows, ffn_shard, with_units=True)
         for h, e, row0, nb, z, kt0, nk, srow in units[(units[:, 0] > 0) & (units[:, 4] >= 1)]:
             end = min(row0 + h, int(offs[e + 1]))

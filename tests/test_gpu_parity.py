@@ -236,6 +236,48 @@ def test_expert_ffn_against_oracle(H, I_s, counts):
     assert _rel(yb[:R], ref) < REL_L2
 
 
+@pytest.mark.parametrize("H,I_s,lo,hi,gather", [
+    (1024, 192, 226, 330, False),    # 64 experts, a few hundred rows each: one to three 160-row blocks per expert
+    (1024, 320, 100, 480, True),     # wide spread around the same average, rows read through row_src
+    (2048, 128, 0, 560, False),      # empty experts and experts with four blocks
+])
+def test_expert_ffn_even_row_blocks(H, I_s, lo, hi, gather):
+    """Calls with a few hundred rows per expert run on the tiling with row blocks of 160 rows."""
+    n = 64
+    rng = np.random.default_rng(H + I_s)
+    counts = rng.integers(lo, hi + 1, n)
+    counts[5] = 160       # exactly one block
+    counts[6] = 161       # one row into the second
+    counts[7] = 320
+    counts = counts * (270 * n) // int(counts.sum())   # average of 270 rows whatever the spread
+    counts[5], counts[6], counts[7] = 160, 161, 320
+    offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    R = int(offs[-1])
+    cap = R + 3
+    shard = B.make_shard(n, n, 0, H, I_s, I_s)
+    assert B.moe_debug_tile_rows(cap, shard) == 160
+    assert B.moe_debug_ffn_plan(cap, shard)[:2] == (False, False)
+    wg, wu, wd = I.make_expert_weights(2, I.MoEShape("f", H, n, 1, I_s, True))
+    if gather:
+        k = 2
+        T = (cap + k - 1) // k
+        x = I.make_x(3, T, H)
+        row_src = rng.permutation(T * k)[:cap].astype(np.int32)
+        xp = x[row_src // k]
+        y = _ffn_gpu(xp, offs, shard, wg, wu, wd, gather=(x, row_src, k))
+    else:
+        xp = I.make_x(3, cap, H)
+        y = _ffn_gpu(xp, offs, shard, wg, wu, wd)
+    ref = O.expert_ffn(xp[:R], offs, wg, wu, wd)
+    assert np.all(np.isnan(y[R:])), "rows past R must not be written"
+    assert _rel(y[:R], ref) < REL_L2 and np.abs(y[:R] - ref).max() < MAX_ABS
+    yb = _ffn_gpu(xp, offs, shard, wg, wu, wd, y_bf16=True)
+    assert np.all(np.isnan(yb[R:])) and _rel(yb[:R], ref) < REL_L2
+    # each GEMM alone (operator-level timing flags) gives the same bits as the pair
+    h_only = _ffn_gpu(xp, offs, shard, wg, wu, wd, flags=B.MOE_FFN_SKIP_DOWN)
+    assert np.all(np.isnan(h_only))   # y_perm untouched
+
+
 def test_expert_ffn_streaming_kernel_with_experts_that_need_several_row_passes():
     """24 small experts, three of them with 17 to 33 rows: 26 (expert, pass) units over 256
     workgroups do not divide evenly, so the ranges of the streaming kernel cross from one unit into

@@ -70,3 +70,18 @@ def test_wave_parallel_work_list_equals_the_plain_one(n_local, ncb, nk, max_slic
             assert np.array_equal(dev[live, 8], host[live, 7]), counts
             ends = offs[dev[live, 1] + 1]
             assert np.array_equal(dev[live, 3], ends)
+
+
+@pytest.mark.parametrize("n_local,ncb,max_rows", [(60, 11, 17000), (64, 14, 20000), (4, 8, 2000), (5, 8, 2000),
+                                                  (200, 2, 60000), (1, 3, 700)])
+def test_even_work_list_on_the_device_equals_the_host_one(n_local, ncb, max_rows):
+    rng = np.random.default_rng(n_local * 31 + ncb)
+    for counts in _routings(rng, n_local, max_rows):
+        offs = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+        cap = max(int(offs[-1]), 1) + int(rng.integers(0, 700))
+        dev = B.moe_debug_device_units(torch.from_numpy(offs).cuda(), cap, ncb, 32, -1)
+        torch.cuda.synchronize()
+        dev = dev.cpu().numpy()
+        host = B.moe_debug_even_units(offs, cap, ncb)
+        assert dev.shape[0] == host.shape[0]
+        assert np.array_equal(dev[:, :5], host), counts

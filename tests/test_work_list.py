@@ -2,6 +2,8 @@
 moe_debug_gemm_units.  For any routing, the tiles of all workgroups must cover every routed row of
 every column block exactly once, never reach into another expert's rows, and the grid bound the
 launcher uses must hold."""
+import ctypes
+
 import numpy as np
 
 from paper_2508_19373_amd import binding as B
@@ -112,3 +114,64 @@ def test_invalid_arguments():
     offs = np.array([0, 5, 9], dtype=np.int32)
     assert L.moe_debug_gemm_units(offs.ctypes.data, 2, 8, 1, out.ctypes.data, 64) == B.MOE_ERR_INVALID_ARG  # last > cap
     assert L.moe_debug_gemm_units(offs.ctypes.data, 2, 16, 1, out.ctypes.data, 2) == B.MOE_ERR_WORKSPACE
+
+
+def _check_even_cover(rows, cap_rows, ncb):
+    offs = _offsets(rows)
+    units = B.moe_debug_even_units(offs, cap_rows, ncb)
+    cover = np.zeros((max(int(offs[-1]), 1), ncb), dtype=np.int32)
+    for h, e, row0, row_end, nb in units.tolist():
+        if h == 0:
+            continue
+        assert h == 160 and 0 <= e < len(rows) and 0 <= nb < ncb
+        assert offs[e] <= row0 < row_end == offs[e + 1] and (row0 - offs[e]) % 160 == 0
+        cover[row0:min(row0 + h, row_end), nb] += 1
+    assert (cover[:int(offs[-1])] == 1).all()
+    return units
+
+
+def test_even_row_blocks_cover_every_row_once():
+    rng = np.random.default_rng(99)
+    for trial in range(80):
+        n_local = int(rng.integers(1, 70))
+        ncb = int(rng.integers(1, 9))
+        if trial % 3 == 0:
+            rows = rng.integers(0, 700, n_local) * (rng.random(n_local) < 0.8)
+        elif trial % 3 == 1:
+            rows = rng.choice([1, 159, 160, 161, 319, 320, 321, 480, 481], n_local)
+        else:
+            rows = rng.multinomial(int(rng.integers(1, 20000)), rng.dirichlet(np.ones(n_local)))
+        rows = rows.astype(np.int64)
+        _check_even_cover(rows, int(rows.sum()) + int(rng.integers(0, 300)), ncb)
+    units = _check_even_cover(np.zeros(5, dtype=np.int64), 0, 3)
+    assert (units[:, 0] == 0).all()
+
+
+def test_even_row_blocks_of_one_column_block_are_neighbours_on_one_xcd():
+    # 60 experts of 250 to 300 rows, 11 column blocks (the gate/up projection of a 60 x 1408 layer at
+    # 4096 tokens): the two row blocks of an (expert, column block) run side by side on one XCD, so
+    # the second reader of the weight panel finds it in that XCD's L2
+    rng = np.random.default_rng(3)
+    rows = rng.integers(250, 301, 60)
+    units = _check_even_cover(rows, int(rows.sum()), 11)
+    assert (units[:, 0] == 160).sum() == 60 * 11 * 2
+    pairs = same = 0
+    for x in range(8):
+        u = units[x::8]
+        u = u[u[:, 0] > 0]
+        for a, b in zip(u[:-1], u[1:]):
+            if a[2] != b[2] and a[1] == b[1] and a[4] == b[4]:
+                same += 1
+        pairs += len(u) // 2
+    assert same >= 0.95 * pairs
+
+
+def test_tile_rows_rule():
+    qwen = B.make_shard(60, 60, 0, 2048, 1408, 1408)
+    assert B.moe_debug_tile_rows(4096 * 4, qwen) == 160      # 273 rows per expert
+    assert B.moe_debug_tile_rows(2048 * 4, qwen) == 256      # 137
+    assert B.moe_debug_tile_rows(8192 * 4, qwen) == 256      # 546
+    assert B.moe_debug_tile_rows(4096 * 4, B.make_shard(60, 30, 0, 2048, 1408, 1408)) == 256   # too few tiles to be HBM-bound
+    assert B.moe_debug_tile_rows(4096 * 2, B.make_shard(8, 8, 0, 4096, 14336, 14336)) == 256   # 1024 rows per expert
+    assert B.lib().moe_debug_tile_rows(-1, ctypes.byref(qwen)) == B.MOE_ERR_INVALID_ARG
+    assert B.lib().moe_debug_tile_rows(-1, None) == B.MOE_ERR_INVALID_ARG
