@@ -6,9 +6,11 @@ A step is one pass of the whole hot path (route -> permute -> grouped SwiGLU FFN
 resident in HBM.  Prints ONE JSON line: whole-layer throughput in bf16 TFLOP/s (algorithmic
 FLOPs only), ms per step, a roofline object for the dominant kernel measured live with
 events on the launch stream, and the CPU oracle timed on a bounded sample of the same
-workload.
+workload.  The line's `also` object holds the same measurement (50 steps after 30) of two more
+shapes taken in the same process: a decode shape (Mixtral-sized, 16 tokens: HBM-bound) and the
+Qwen-sized prefill, the shape furthest from its roofline.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload mixtral_prefill]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload mixtral_prefill] [--no-also]
 """
 from __future__ import annotations
 
@@ -32,6 +34,9 @@ MEASURED_TRAFFIC_BYTES = {
     "mixtral_prefill": (1958869.5 * 2.0 + 232964.5) * 1024,
     "mixtral_decode": (936905.7 * 2.0 + 898.8) * 1024,
 }
+
+# measured after the main workload in the same run (`also` in the JSON line)
+ALSO_WORKLOADS = ("mixtral_decode", "qwen_prefill")
 
 # name -> (inputs.WORKLOADS key, token count, description)
 WORKLOADS = {
@@ -65,49 +70,10 @@ def time_events(fn, iters, torch):
     return start.elapsed_time(end) / iters
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="mixtral_prefill", choices=sorted(WORKLOADS))
-    ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run plain 1 GiB device copies, to scale FETCH_SIZE / WRITE_SIZE counters under rocprofv3")
-    ap.add_argument("--permuted-copy", action="store_true",
-                    help="moe_permute writes x_perm and moe_expert_ffn reads it (default: the layer's own choice)")
-    ap.add_argument("--gather-rows", action="store_true",
-                    help="the FFN gathers its rows of x through row_src (default: the layer's own choice)")
-    ap.add_argument("--no-overlap-shared", action="store_true",
-                    help="run the shared expert after the routed experts instead of beside them on a second stream")
-    ap.add_argument("--graph", choices=["auto", "on", "off"], default="auto",
-                    help="replay the layer as one HIP graph (auto: when an eager step takes < 1 ms)")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens the oracle is timed on (0 = auto)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py measures one GPU's shard: this build has no multi-GPU path; run with --gpus 1")
-
-    import numpy as np
-    import torch
-    from paper_2508_19373_amd import binding as B
-    from paper_2508_19373_amd import inputs as I
-    from paper_2508_19373_amd.layer import ExpertShardLayer, bf16_tensor
-
-    if not torch.cuda.is_available():
-        sys.exit("bench.py needs a GPU")
-    B.lib()  # fail loudly when the HIP library is missing
-    torch.cuda.set_device(0)
-
-    if args.copy_calibration:  # a kernel of known traffic: reads 1 GiB, writes 1 GiB per launch
-        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
-    key, T, desc = WORKLOADS[args.workload]
+def measure(workload, steps, warmup, args, torch, np, B, I, ExpertShardLayer, bf16_tensor):
+    """One workload: whole-layer time over `steps` steps after `warmup`, per-call breakdown, and
+    the roofline of its dominant kernel.  Returns a dict of everything the JSON line needs."""
+    key, T, desc = WORKLOADS[workload]
     shape, _ = I.WORKLOADS[key]
     t0 = time.time()
     li = I.make_layer_inputs(shape, T, args.seed)
@@ -121,14 +87,14 @@ def main():
         return layer.forward(x, logits)
 
     def timed(fn):
-        for _ in range(args.warmup):
+        for _ in range(warmup):
             fn()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps):
+        for _ in range(steps):
             fn()
         torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / args.steps
+        return (time.perf_counter() - t0) * 1e3 / steps
 
     eager_ms = timed(step)
     ms_per_step, mode = eager_ms, "eager"
@@ -139,7 +105,7 @@ def main():
     # per-step spread (median and minimum over the same number of steps, one event pair per step) and the
     # device copy rate of this GPU, for reading the HBM fractions against something measured
     run_step = graph.replay if mode == "hip-graph" else step
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     torch.cuda.synchronize()
     for a, b in evs:
         a.record()
@@ -162,7 +128,7 @@ def main():
     # ---- per-call breakdown and the dominant kernel, events on the launch stream
     k, H, E = shape.top_k, shape.hidden, shape.n_experts
     rflags = (B.MOE_RENORM_TOPK if shape.renorm else 0) | (B.MOE_LOGITS_GIVEN if logits is not None else 0)
-    it = max(5, min(args.steps, 50))
+    it = max(5, min(steps, 50))
     br = {}
     br["route_topk"] = time_events(lambda: B.moe_route_topk(x, layer.w_router, layer.logits, T, H, E, k, rflags,
                                                             layer.topk_idx, layer.topk_w), it, torch)
@@ -198,23 +164,86 @@ def main():
     intensity = g1_flops / g1_bytes
     decode = B.moe_debug_ffn_plan(T * k, layer.ffn_shard)[0]   # GEMM1 takes the weight-streaming kernel
     kname = ("moe::gw::grouped_walk_kernel<..., GATEUP> (GEMM1 + SwiGLU, weight streaming)" if decode
-             else "moe::gg::grouped_gemm_dlds_kernel<256, GATEUP> (GEMM1 + SwiGLU)")
+             else ("moe::gg::grouped_gemm_even_kernel<256, GATEUP> (GEMM1 + SwiGLU, 160-row blocks)"
+                   if B.moe_debug_tile_rows(T * k, layer.ffn_shard) == 160
+                   else "moe::gg::grouped_gemm_dlds_kernel<256, GATEUP> (GEMM1 + SwiGLU)"))
     if intensity > PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
         ach = g1_flops / (g1_ms * 1e-3) / 1e12
         roofline = {"kernel": kname, "bound": "mfma", "achieved": ach,
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(workload),
                     "ms": g1_ms, "flops_per_launch": g1_flops, "algorithmic_bytes_per_launch": g1_bytes}
     else:
         ach = g1_bytes / (g1_ms * 1e-3) / 1e9
         roofline = {"kernel": kname, "bound": "hbm", "achieved": ach,
                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(workload),
                     "ms": g1_ms, "bytes_per_launch": g1_bytes}
 
+    # the kernel's rate against both peaks (its own intensity decides which one `frac` is taken from)
+    roofline["frac_of_mfma_peak"] = g1_flops / (g1_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
+    roofline["frac_of_hbm_peak"] = g1_bytes / (g1_ms * 1e-3) / 1e9 / PEAK_HBM_GBS
+    roofline["flop_per_byte"] = intensity
     if 2.0 * active * H * I_s * 2 < 256e6:
         roofline["note"] = ("GEMM1's weights (%.0f MB) fit the 256 MB last-level cache and are replayed from one "
                             "buffer here: not an HBM measurement" % (2.0 * active * H * I_s * 2 / 1e6))
+
+    return dict(shape=shape, T=T, desc=desc, li=li, layer=layer, x=x, logits=logits, ms_per_step=ms_per_step, mode=mode,
+                eager_ms=eager_ms, step_median_ms=step_median_ms, step_min_ms=step_min_ms, copy_gbs=copy_gbs,
+                flops=flops, min_bytes=min_bytes, R=R, active=active, tflops=tflops, gbs=gbs, br=br, gen_s=gen_s,
+                roofline=roofline, k=k, H=H, E=E, I_s=I_s)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--workload", default="mixtral_prefill", choices=sorted(WORKLOADS))
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain 1 GiB device copies, to scale FETCH_SIZE / WRITE_SIZE counters under rocprofv3")
+    ap.add_argument("--permuted-copy", action="store_true",
+                    help="moe_permute writes x_perm and moe_expert_ffn reads it (default: the layer's own choice)")
+    ap.add_argument("--gather-rows", action="store_true",
+                    help="the FFN gathers its rows of x through row_src (default: the layer's own choice)")
+    ap.add_argument("--no-overlap-shared", action="store_true",
+                    help="run the shared expert after the routed experts instead of beside them on a second stream")
+    ap.add_argument("--graph", choices=["auto", "on", "off"], default="auto",
+                    help="replay the layer as one HIP graph (auto: when an eager step takes < 1 ms)")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens the oracle is timed on (0 = auto)")
+    ap.add_argument("--no-also", action="store_true",
+                    help="skip the two extra workloads (a decode shape and the Qwen-sized prefill) measured after the main one")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU's shard: this build has no multi-GPU path; run with --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2508_19373_amd import binding as B
+    from paper_2508_19373_amd import inputs as I
+    from paper_2508_19373_amd.layer import ExpertShardLayer, bf16_tensor
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    B.lib()  # fail loudly when the HIP library is missing
+    torch.cuda.set_device(0)
+
+    if args.copy_calibration:  # a kernel of known traffic: reads 1 GiB, writes 1 GiB per launch
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    m = measure(args.workload, args.steps, args.warmup, args, torch, np, B, I, ExpertShardLayer, bf16_tensor)
+    shape, T, desc, li, layer, x, logits = m["shape"], m["T"], m["desc"], m["li"], m["layer"], m["x"], m["logits"]
+    ms_per_step, mode, eager_ms = m["ms_per_step"], m["mode"], m["eager_ms"]
+    step_median_ms, step_min_ms, copy_gbs = m["step_median_ms"], m["step_min_ms"], m["copy_gbs"]
+    flops, min_bytes, R, active, tflops, gbs = m["flops"], m["min_bytes"], m["R"], m["active"], m["tflops"], m["gbs"]
+    br, gen_s, roofline, k, H, E, I_s = m["br"], m["gen_s"], m["roofline"], m["k"], m["H"], m["E"], m["I_s"]
 
     # ---- CPU baseline: the oracle as it stands on a bounded token sample
     cpu = None
@@ -256,6 +285,26 @@ def main():
         "launch_mode": mode, "eager_ms_per_step": eager_ms, "step_ms_median": step_median_ms,
         "step_ms_min": step_min_ms, "device_copy_gbs": copy_gbs, "breakdown_ms": br, "input_gen_s": gen_s, "roofline": roofline, "cpu_baseline": cpu,
     }
+    # ---- two more shapes in the same process, so that one run covers a decode shape (HBM-bound) and
+    # the prefill shape furthest from its roofline beside the headline
+    if not args.no_also:
+        del m, layer, x, logits, li
+        torch.cuda.empty_cache()
+        also = {}
+        for w in ALSO_WORKLOADS:
+            if w == args.workload:
+                continue
+            # (their own step counts: short runs of these small layers are dominated by the clock settling)
+            a = measure(w, 50, 30, args, torch, np, B, I, ExpertShardLayer, bf16_tensor)
+            r = a["roofline"]
+            also[w] = {"workload": a["desc"], "us_per_layer": a["ms_per_step"] * 1e3, "launch_mode": a["mode"],
+                       "tflops": a["tflops"], "pct_mfma_peak": 100.0 * a["tflops"] / PEAK_BF16_TFLOPS,
+                       "min_bytes_gbs": a["gbs"], "pct_hbm_peak": 100.0 * a["gbs"] / PEAK_HBM_GBS,
+                       "bound": r["bound"], "frac": r["frac"], "kernel": r["kernel"], "kernel_ms": r["ms"],
+                       "breakdown_ms": a["br"]}
+            del a
+            torch.cuda.empty_cache()
+        out["also"] = also
     print(json.dumps(out))
 
 

@@ -11,6 +11,7 @@ from oracle import moe_oracle as O
 from paper_2508_19373_amd import binding as B
 from paper_2508_19373_amd import inputs as I
 from paper_2508_19373_amd.layer import ExpertShardLayer, bf16_bits, bf16_tensor
+from guards import Guards
 from sampling import stratified_tokens
 
 pytestmark = pytest.mark.gpu
@@ -69,6 +70,7 @@ def test_full_size_against_oracle(key, T):
     print("case", key, T, flush=True)
     if _cache["layer"] is None:
         _cache["layer"] = ExpertShardLayer.from_inputs(li, out_f32=True, max_tokens=8192 if "mixtral" in key else 4096)
+        _cache["guards"] = Guards().wrap_layer(_cache["layer"])   # bands before and behind every buffer the layer owns
     layer = _cache["layer"]
     x = bf16_tensor(li.x)
     logits_in = None if li.logits is None else torch.from_numpy(li.logits).cuda()
@@ -77,7 +79,7 @@ def test_full_size_against_oracle(key, T):
     B.moe_combine(layer.y_perm, layer.slot_row, layer.topk_w, T, k, shape.hidden,
                   layer.y_shared if layer.shared is not None else None,
                   x if layer.w_shared_gate is not None else None, layer.w_shared_gate, ybf, 0)
-    torch.cuda.synchronize()
+    _cache["guards"].check()
     ybf = ybf.float().cpu().numpy().astype(np.float64)
 
     # ---- integers, in full

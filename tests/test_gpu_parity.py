@@ -10,6 +10,7 @@ import torch
 from oracle import moe_oracle as O
 from paper_2508_19373_amd import binding as B
 from paper_2508_19373_amd import inputs as I
+from guards import Guards
 from paper_2508_19373_amd.layer import ExpertShardLayer, bf16_bits, bf16_tensor
 
 pytestmark = pytest.mark.gpu
@@ -30,9 +31,10 @@ def _rel(a, b):
 
 
 def _route_gpu(x_bits, w_router, logits, T, H, E, k, renorm):
-    d_logits = torch.empty((max(T, 1), E), dtype=torch.float32, device="cuda")
-    idx = torch.full((max(T, 1), k), -7, dtype=torch.int32, device="cuda")
-    w = torch.empty((max(T, 1), k), dtype=torch.float32, device="cuda")
+    g = Guards()
+    d_logits = g.empty((max(T, 1), E), torch.float32)
+    idx = g.empty((max(T, 1), k), torch.int32, fill=-7)
+    w = g.empty((max(T, 1), k), torch.float32)
     flags = B.MOE_RENORM_TOPK if renorm else 0
     if logits is not None:
         d_logits[:T].copy_(_dev(logits))
@@ -40,7 +42,7 @@ def _route_gpu(x_bits, w_router, logits, T, H, E, k, renorm):
         B.moe_route_topk(None, None, d_logits, T, H, E, k, flags, idx, w)
     else:
         B.moe_route_topk(bf16_tensor(x_bits), _dev(w_router), d_logits, T, H, E, k, flags, idx, w)
-    torch.cuda.synchronize()
+    g.check()
     return d_logits[:T].cpu().numpy(), idx[:T].cpu().numpy(), w[:T].cpu().numpy()
 
 
@@ -105,15 +107,16 @@ def _permute_gpu(x_bits, idx, shard):
     T, k = idx.shape
     H = x_bits.shape[1]
     cap = max(T * k, 1)
-    x_perm = torch.zeros((cap, H), dtype=torch.bfloat16, device="cuda")
-    offs = torch.full((shard.n_local_experts + 1,), -5, dtype=torch.int32, device="cuda")
-    row_src = torch.full((cap,), -5, dtype=torch.int32, device="cuda")
-    slot_row = torch.full((cap,), -5, dtype=torch.int32, device="cuda")
-    ws = torch.empty(max(B.moe_workspace_bytes(T, k, shard), 1), dtype=torch.uint8, device="cuda")
+    g = Guards()
+    x_perm = g.empty((cap, H), torch.bfloat16, fill=0)
+    offs = g.empty((shard.n_local_experts + 1,), torch.int32, fill=-5)
+    row_src = g.empty((cap,), torch.int32, fill=-5)
+    slot_row = g.empty((cap,), torch.int32, fill=-5)
+    ws = g.empty(max(B.moe_workspace_bytes(T, k, shard), 1), torch.uint8)
     x_dev = bf16_tensor(x_bits) if T else torch.zeros((1, H), dtype=torch.bfloat16, device="cuda")
     idx_dev = _dev(idx) if T else torch.zeros((1, k), dtype=torch.int32, device="cuda")
     B.moe_permute(x_dev, idx_dev, T, k, shard, x_perm, offs, row_src, slot_row, ws)
-    torch.cuda.synchronize()
+    g.check()
     return offs.cpu().numpy(), row_src.cpu().numpy(), slot_row.cpu().numpy(), bf16_bits(x_perm)
 
 
@@ -180,10 +183,10 @@ def test_permute_is_deterministic():
 def _ffn_gpu(x_perm_bits, offs, shard, wg, wu, wd, y_bf16=False, gather=None, flags=0):
     """gather = (x_bits [T,H], row_src [cap], k): run moe_expert_ffn_gather on x instead of the permuted copy."""
     cap = x_perm_bits.shape[0]
-    h_ws = torch.empty((cap, shard.inter_slice), dtype=torch.bfloat16, device="cuda")
-    y = torch.full((cap, shard.hidden), float("nan"), dtype=torch.bfloat16 if y_bf16 else torch.float32,
-                   device="cuda")
-    ws = torch.empty(max(B.moe_ffn_workspace_bytes(cap, shard), 16), dtype=torch.uint8, device="cuda")
+    g = Guards()
+    h_ws = g.empty((cap, shard.inter_slice), torch.bfloat16)
+    y = g.empty((cap, shard.hidden), torch.bfloat16 if y_bf16 else torch.float32, fill=float("nan"))
+    ws = g.empty(max(B.moe_ffn_workspace_bytes(cap, shard), 16), torch.uint8)
     if gather is not None:
         x_bits, row_src, k = gather
         B.moe_expert_ffn_gather(bf16_tensor(x_bits), _dev(row_src), k, _dev(offs), cap, shard, bf16_tensor(wg),
@@ -192,7 +195,7 @@ def _ffn_gpu(x_perm_bits, offs, shard, wg, wu, wd, y_bf16=False, gather=None, fl
     else:
         B.moe_expert_ffn(bf16_tensor(x_perm_bits), _dev(offs), cap, shard, bf16_tensor(wg), bf16_tensor(wu),
                          bf16_tensor(wd), h_ws, y, ws, flags | (B.MOE_Y_PERM_BF16 if y_bf16 else 0))
-    torch.cuda.synchronize()
+    g.check()
     return y.float().cpu().numpy().astype(np.float64)
 
 
@@ -435,10 +438,11 @@ def test_combine_against_oracle(y_bf16, out_f32, with_shared):
 # ------------------------------------------------------------------ whole layer, small shapes
 def _run_layer(li, **kw):
     layer = ExpertShardLayer.from_inputs(li, **kw)
+    g = Guards().wrap_layer(layer)
     x = bf16_tensor(li.x)
     logits = None if li.logits is None else _dev(li.logits)
     y = layer.forward(x, logits).float().cpu().numpy().astype(np.float64)
-    torch.cuda.synchronize()
+    g.check()
     return layer, y
 
 

@@ -16,6 +16,7 @@ from oracle import moe_oracle as O
 from paper_2508_19373_amd import inputs as I
 from paper_2508_19373_amd.latency_table import legal_shards
 from paper_2508_19373_amd.layer import ExpertShardLayer, bf16_tensor
+from guards import Guards
 from sampling import stratified_tokens
 
 pytestmark = pytest.mark.gpu
@@ -72,7 +73,9 @@ def _run_shard(m, base, tp, p, ep, q, x, T):
                              shared=dev_sh, w_shared_gate=m["w_sg"] if dev_sh is not None else None,
                              inter_shared_full=base.inter_shared, inter_shared_slice=base.inter_shared // tp,
                              max_tokens=T, out_f32=True)
+    g = Guards().wrap_layer(layer)
     y = layer.forward(x).cpu().numpy().astype(np.float64)
+    g.check()
     return layer, y, host, host_sh
 
 
