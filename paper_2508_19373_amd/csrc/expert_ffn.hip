@@ -192,12 +192,24 @@ hipError_t launch_pair_decode(const void* x_perm, RowMap rows, const int32_t* ex
   return hipGetLastError();
 }
 
+// Rows the fullest local expert is planned for.  A shard that holds every expert gets exactly the
+// capacity, and only its spread over the experts is open: the average plus two sigma.  An
+// expert-parallel shard's share of the batch follows the routing ("Expert Parallelism": load
+// imbalance), and the shard that sets the latency of the step is the one that got more than its
+// share, so it is planned for twice the balanced share (under Zipf(1.2) popularity the first of four
+// shards receives 55 % of the rows, 2.2 times a quarter), never more than the whole capacity.
+inline double planned_rows_hi(int cap_rows, int est_rows, int n_local) {
+  double avg = (double)est_rows / n_local;
+  if (n_local == 1 && est_rows == cap_rows) return avg;  // one expert that takes every row
+  if (est_rows < cap_rows) avg = fmin(2.0 * avg, (double)cap_rows / n_local);
+  return avg + 2.0 * sqrt(avg);
+}
+
 // MT = 1 (16 activation rows per pass) when the fullest expert is expected to stay within 16 rows
-// (two-sigma margin on the average; certain when the whole capacity is 16 rows): it keeps twice
-// the bytes in flight, and an expert with more rows only pays another pass over its own weights.
+// (certain when the whole capacity is 16 rows): it keeps twice the bytes in flight, and an expert
+// with more rows only pays another pass over its own weights.
 inline int decode_mt(int cap_rows, int est_rows, int n_local) {
-  const double avg = (double)est_rows / n_local;
-  return (cap_rows <= 16 || avg + 2.0 * sqrt(avg) <= 16.0) ? 1 : 2;
+  return (cap_rows <= 16 || planned_rows_hi(cap_rows, est_rows, n_local) <= 16.0) ? 1 : 2;
 }
 
 // Which kernel family runs one of the two GEMMs: the weight-streaming walk (decode regime) or the
@@ -216,9 +228,8 @@ inline int decode_mt(int cap_rows, int est_rows, int n_local) {
 //          k-tile of a full 256-row tile); never faster than 1.2 PFLOP/s overall.
 inline bool prefer_walk(int cap_rows, int est_rows, int n_local, int n_out, int K, bool gateup) {
   const double mats = gateup ? 2.0 : 1.0;
-  const double avg = (double)est_rows / n_local;
   const bool exact = n_local == 1 && est_rows == cap_rows;  // one expert that takes every row
-  const double rows_hi = exact ? avg : avg + 2.0 * sqrt(avg);
+  const double rows_hi = planned_rows_hi(cap_rows, est_rows, n_local);
   const int mt = decode_mt(cap_rows, est_rows, n_local);
   const double passes = ceil(rows_hi / (16.0 * mt));
   const double bytes = mats * n_local * (double)n_out * K * 2.0;

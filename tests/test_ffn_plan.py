@@ -53,6 +53,20 @@ def test_expert_parallel_shard_is_planned_on_its_expected_rows():
     assert B.moe_debug_ffn_plan(16, ep8)[2] == 1            # capacity itself is 16 rows
 
 
+def test_expert_parallel_shard_is_planned_for_more_than_its_balanced_share():
+    # two of eight experts (EP = 4).  The shard that sets the step's latency is the one that received
+    # more than a quarter of the rows, so rows per pass and kernel family are chosen for twice the
+    # balanced share: 32 tokens x top-2 = 64 assignments, 16 expected here, planned for 32
+    ep4 = _shard(8, 2, **MIXTRAL)
+    full = _shard(8, 8, **MIXTRAL)
+    assert B.moe_debug_ffn_plan(32, ep4)[:3] == (True, True, 1)     # 16 tokens: 8 rows expected, 16 planned
+    assert B.moe_debug_ffn_plan(64, ep4)[:3] == (True, False, 2)    # 32 tokens: 32 rows per pass, down projection tiled
+    assert B.moe_debug_ffn_plan(128, ep4)[0] is False               # 64 tokens: gate/up on the tiled kernel
+    # the unsharded layer at the same rows per expert keeps 16 rows per pass and the streaming kernel
+    assert B.moe_debug_ffn_plan(64, full)[:3] == (True, True, 1)
+    assert B.moe_debug_ffn_plan(128, full)[0] is True
+
+
 def _offsets(counts):
     import numpy as np
     return np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)

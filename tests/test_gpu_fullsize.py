@@ -27,7 +27,9 @@ N_SAMPLE = 512
 RAW_BF16_GATE = lambda key: key in ("mixtral_tp4", "qwen", "qwen_tp4_ep2")
 
 CASES = [("mixtral", 16), ("mixtral", 4096), ("mixtral_tp4", 64), ("mixtral_tp4", 8192),
-         ("mixtral_ep4_hot", 8192), ("mixtral_ep4_cold", 8192), ("qwen", 32), ("qwen", 4096),
+         ("mixtral_ep4_hot", 8192), ("mixtral_ep4_cold", 8192),
+         # decode-sized batches under the same skew: the hot shard gets about twice its balanced share
+         ("mixtral_ep4_hot", 32), ("mixtral_ep4_hot", 64), ("mixtral_ep4_cold", 64), ("qwen", 32), ("qwen", 4096),
          ("qwen2_57b", 32), ("qwen2_57b", 4096),
          # hybrid shards (fewer experts AND a slice of the intermediate dimension), one per model
          ("mixtral_tp2_ep2", 64), ("mixtral_tp2_ep2", 4096),
@@ -105,9 +107,9 @@ def test_full_size_against_oracle(key, T):
     torch.cuda.synchronize()
     assert np.array_equal(bf16_bits(xp[:R]), x_perm)
     del xp
-    if key == "mixtral_ep4_hot":
+    if key == "mixtral_ep4_hot" and T >= 1024:
         assert R > 0.5 * T * k  # experts 0,1 carry more than half of all rows under Zipf(1.2)
-    if key == "mixtral_ep4_cold":
+    if key == "mixtral_ep4_cold" and T >= 1024:
         assert R < 0.15 * T * k
 
     # ---- floating point, on a token sample (GPU routing decisions, oracle arithmetic)
