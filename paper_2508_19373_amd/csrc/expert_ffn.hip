@@ -220,12 +220,18 @@ inline int decode_mt(int cap_rows, int est_rows, int n_local) {
 // column blocks per row block: 14 CUs, which is why such a launch is also cut along K).
 // Estimates in seconds, from measured rates on MI355X:
 //   walk   passes * (bytes / rate + 5 us), rate 6.0 / 5.4 TB/s (GEMM1 / GEMM2) at 16 rows per pass,
-//          5.6 / 4.9 TB/s at 32, 3 TB/s for K extents only the generic streaming kernel covers;
-//          passes from the rows of the fullest expert (two-sigma margin);
-//   tiled  rounds * (tile time + 8 us), rounds = tiles * slices / 256, at least one; tile time is
-//          the larger of streaming the tile's weight panel (latency-bound 45 GB/s per compute unit,
-//          less when the busy units together would exceed 5.4 TB/s) and its MFMA pace (1.3 us per
-//          k-tile of a full 256-row tile); never faster than 1.2 PFLOP/s overall.
+//          5.3 / 4.9 TB/s at 32, 3 TB/s for K extents only the generic streaming kernel covers;
+//          passes from the rows of the fullest expert (planned_rows_hi);
+//   tiled  rounds * (tile time + 8 us), rounds = tiles * slices / 256, at least one; tile time is the
+//          larger of streaming the tile's weight panel latency-bound (45 GB/s per compute unit) and
+//          its MFMA pace (1.3 us per k-tile of a full 256-row tile); never faster than 1.2 PFLOP/s
+//          overall.  What HBM allows when all compute units stream at once: for the gate/up
+//          projection all panels together at 5.7 TB/s + 4 us (measured 5.4-5.9 TB/s); for the down
+//          projection the per-unit rate is capped at 5.4 TB/s / busy units inside the tile time
+//          (its partial sums and their addition ride on the 8 us).
+// (Measured, Mixtral TP=4 shard at 48-64 tokens: gate/up streaming with 32 rows per pass 90.5-91.8 us,
+// tiled 86.2-86.6; with 16 rows per pass at 16-32 tokens 80.5-81.8 against 85.7.  Qwen1.5 down
+// projection at 64-128 tokens: streaming 68.0 / 73.7 us, tiled 61.8 / 66.0.)
 inline bool prefer_walk(int cap_rows, int est_rows, int n_local, int n_out, int K, bool gateup) {
   const double mats = gateup ? 2.0 : 1.0;
   const bool exact = n_local == 1 && est_rows == cap_rows;  // one expert that takes every row
@@ -234,15 +240,24 @@ inline bool prefer_walk(int cap_rows, int est_rows, int n_local, int n_out, int 
   const double passes = ceil(rows_hi / (16.0 * mt));
   const double bytes = mats * n_local * (double)n_out * K * 2.0;
   const double rate = gw::plan_for(K, mt).nw == 0 ? 3.0e12
-                                                  : (mt == 1 ? (gateup ? 6.0e12 : 5.4e12) : (gateup ? 5.6e12 : 4.9e12));
+                                                  : (mt == 1 ? (gateup ? 6.0e12 : 5.4e12) : (gateup ? 5.3e12 : 4.9e12));
   const double walk = passes * (bytes / rate + 5e-6);
   const int ncb = (n_out + (gateup ? 127 : 255)) / (gateup ? 128 : 256);
   const int slices = gateup ? 1 : gg::k_slices_for(est_rows, n_local, ncb, K, exact);
   const double units = (double)gg::expected_tiles(est_rows, n_local, ncb, exact) * slices;
-  const double per_cu = fmin(45e9, 5.4e12 / fmin(units, 256.0));
   const double k_slice = (double)K / slices;
-  const double tile = fmax(256.0 * k_slice * 2.0 / per_cu, k_slice / 64.0 * 1.3e-6 * fmin(1.0, rows_hi / 256.0)) + 8e-6;
-  const double tiled = fmax(fmax(units / 256.0, 1.0) * tile, 2.0 * mats * est_rows * (double)n_out * K / 1.2e15);
+  const double panel = 256.0 * k_slice * 2.0;  // bytes of weights one tile streams
+  const double mfma_pace = k_slice / 64.0 * 1.3e-6 * fmin(1.0, rows_hi / 256.0);
+  const double by_flops = 2.0 * mats * est_rows * (double)n_out * K / 1.2e15;
+  double tiled;
+  if (gateup) {
+    const double by_rounds = fmax(units / 256.0, 1.0) * (fmax(panel / 45e9, mfma_pace) + 8e-6);
+    const double by_hbm = units * panel / 5.7e12 + 4e-6;  // all tiles together: their panels at the HBM rate
+    tiled = fmax(fmax(by_rounds, by_hbm), by_flops);
+  } else {
+    const double per_cu = fmin(45e9, 5.4e12 / fmin(units, 256.0));
+    tiled = fmax(fmax(units / 256.0, 1.0) * (fmax(panel / per_cu, mfma_pace) + 8e-6), by_flops);
+  }
   return walk < tiled;
 }
 
