@@ -168,10 +168,13 @@ def test_even_row_blocks_of_one_column_block_are_neighbours_on_one_xcd():
 
 def test_tile_rows_rule():
     qwen = B.make_shard(60, 60, 0, 2048, 1408, 1408)
+    # rows per expert just below one or two blocks of 160 rows
     assert B.moe_debug_tile_rows(4096 * 4, qwen) == 160      # 273 rows per expert
-    assert B.moe_debug_tile_rows(2048 * 4, qwen) == 256      # 137
+    assert B.moe_debug_tile_rows(2048 * 4, qwen) == 160      # 137
+    assert B.moe_debug_tile_rows(3072 * 4, qwen) == 256      # 205: a second block for most experts, nothing saved
+    assert B.moe_debug_tile_rows(1536 * 4, qwen) == 256      # 102
     assert B.moe_debug_tile_rows(8192 * 4, qwen) == 256      # 546
-    assert B.moe_debug_tile_rows(4096 * 4, B.make_shard(60, 30, 0, 2048, 1408, 1408)) == 256   # too few tiles to be HBM-bound
+    assert B.moe_debug_tile_rows(4096 * 4, B.make_shard(60, 30, 0, 2048, 1408, 1408)) == 256   # 30 local experts
     assert B.moe_debug_tile_rows(4096 * 2, B.make_shard(8, 8, 0, 4096, 14336, 14336)) == 256   # 1024 rows per expert
     assert B.lib().moe_debug_tile_rows(-1, ctypes.byref(qwen)) == B.MOE_ERR_INVALID_ARG
     assert B.lib().moe_debug_tile_rows(-1, None) == B.MOE_ERR_INVALID_ARG
