@@ -26,8 +26,9 @@ def load_table(path):
         rows = list(csv.DictReader(f))
     for r in rows:
         for k, v in r.items():
-            if k not in ("model", "launch_mode"):
+            if k not in ("model", "launch_mode", "routing"):
                 r[k] = float(v)
+        r.setdefault("routing", "balanced")
     return rows
 
 
@@ -38,7 +39,7 @@ def features_of(row) -> np.ndarray:
                 inter_shared_slice=row["inter_shared"] / tp)
     # derived from the same parameters: expected rows per local expert (decides the regime), the
     # module's FLOPs and the bytes of weights it touches (their ratio is the arithmetic intensity)
-    vals["rows_per_expert"] = row["tokens"] * row["top_k"] / row["n_experts"]
+    vals["rows_per_expert"] = expected_rows(row) / (row["n_experts"] / ep)
     vals["flops"] = module_flops(row)
     vals["weight_bytes"] = weight_bytes(row)
     return np.log2(np.maximum(np.array([vals[k] for k in FEATURES], dtype=np.float64), 1.0))
@@ -57,11 +58,20 @@ def roofline_eta(row, peak_flops=PEAK_FLOPS) -> float:
     return max(1.0, (weight_bytes(row) / PEAK_BYTES) / (module_flops(row) / peak_flops))
 
 
+def expected_rows(row) -> float:
+    """Routed rows of the shard, known before the run: its balanced share T*k/E_e, or, under a
+    skewed expert popularity, the share that popularity gives the shard's experts (the table
+    records it in `routed_rows`; a simulator would compute it from the popularity it assumes)."""
+    if row.get("routing", "balanced") != "balanced" and "routed_rows" in row:
+        return float(row["routed_rows"])
+    return row["tokens"] * row["top_k"] / row["ep"]
+
+
 def module_flops(row) -> float:
     """F_module: algorithmic FLOPs of the shard's Expert module, expected routed rows."""
     T, H, E, k = row["tokens"], row["hidden"], row["n_experts"], row["top_k"]
     I_s, I_sh = row["inter"] / row["tp"], row["inter_shared"] / row["tp"]
-    rows = T * k / row["ep"]  # expected routed rows of the shard (known before the run)
+    rows = expected_rows(row)
     return 2.0 * T * H * E + 6.0 * rows * H * I_s + (6.0 * T * H * I_sh + 2.0 * T * H if I_sh else 0.0)
 
 
@@ -110,3 +120,49 @@ def holdout_error(rows, *, test_fraction=0.2, seed=0, **kw):
     meas = np.array([r["us_per_layer"] for r in test])
     err = np.abs(pred - meas) / meas
     return float(err.mean()), float(err.max()), n_test
+
+
+def group_holdout_error(rows, key, **kw):
+    """Leave-one-group-out: for every value of `key(row)` fit on all other rows and predict that
+    group's.  Returns {group: (mean relative error, max relative error, n)}.  With key = the shard
+    (model, E_t, E_e) this asks what the paper's simulator is for: the latency of a configuration
+    that was not measured, from those that were; with key = the model, a model never seen."""
+    groups = {}
+    for i, r in enumerate(rows):
+        groups.setdefault(key(r), []).append(i)
+    out = {}
+    for g, idx in groups.items():
+        held = set(idx)
+        train = [r for i, r in enumerate(rows) if i not in held]
+        test = [rows[i] for i in idx]
+        model = fit(train, **kw)
+        pred = model.predict_us(test)
+        meas = np.array([r["us_per_layer"] for r in test])
+        err = np.abs(pred - meas) / meas
+        out[g] = (float(err.mean()), float(err.max()), len(idx))
+    return out
+
+
+def report(path):
+    """Hold-out errors of the table at `path`, as text (what the design doc quotes)."""
+    rows = load_table(path)
+    lines = ["%d rows" % len(rows)]
+    rnd = [holdout_error(rows, seed=s, n_estimators=100) for s in range(6)]
+    lines.append("random 20 %% hold-out, 6 splits: mean %.1f %% (%.1f-%.1f), max %.1f %%"
+                 % (100 * np.mean([r[0] for r in rnd]), 100 * min(r[0] for r in rnd), 100 * max(r[0] for r in rnd),
+                    100 * max(r[1] for r in rnd)))
+    by_shard = group_holdout_error(rows, lambda r: (r["model"], r["tp"], r["ep"]), n_estimators=60)
+    means = [v[0] for v in by_shard.values()]
+    worst = max(by_shard.items(), key=lambda kv: kv[1][0])
+    lines.append("leave-one-shard-out, %d shards: mean of shard means %.1f %%, worst shard %s mean %.1f %% max %.1f %%, "
+                 "largest single error %.1f %%" % (len(by_shard), 100 * np.mean(means), worst[0], 100 * worst[1][0],
+                                                   100 * worst[1][1], 100 * max(v[1] for v in by_shard.values())))
+    by_model = group_holdout_error(rows, lambda r: r["model"], n_estimators=60)
+    for m, (mean, mx, n) in by_model.items():
+        lines.append("leave-one-model-out, %s (%d rows): mean %.1f %%, max %.1f %%" % (m, n, 100 * mean, 100 * mx))
+    return "\n".join(lines)
+
+
+if __name__ == "__main__":
+    import sys
+    print(report(sys.argv[1]))

@@ -13,10 +13,14 @@ import csv
 import sys
 import time
 
-FIELDS = ["model", "hidden", "n_experts", "top_k", "inter", "inter_shared", "tp", "ep", "ep_rank", "tokens",
+FIELDS = ["model", "hidden", "n_experts", "top_k", "inter", "inter_shared", "tp", "ep", "ep_rank", "routing", "tokens",
           "routed_rows", "active_experts", "flops", "weight_bytes", "us_per_layer", "launch_mode"]
 
 DEFAULT_TOKENS = (16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512, 768, 1024, 1536, 2048, 3072, 4096, 6144, 8192)
+# Expert-parallel shards are also measured under skewed routing (Zipf(1.2) expert popularity: the load
+# imbalance the paper names as expert parallelism's weakness), on the shard that holds the most
+# popular experts (rank 0) and the one that holds the least popular (last rank), at fewer token counts.
+SKEWED_TOKENS = (16, 64, 256, 1024, 4096, 8192)
 
 
 def legal_shards(shape, max_devices=8):
@@ -114,7 +118,8 @@ def measure(shape, tokens, seed=0, steps=60, warmup=30):
         flops, min_bytes, R, active = algorithmic_work(shape, T, counts)
         rows.append(dict(model=shape.name, hidden=shape.hidden, n_experts=shape.n_experts, top_k=shape.top_k,
                          inter=shape.inter, inter_shared=shape.inter_shared, tp=shape.tp_degree, ep=shape.ep_degree,
-                         ep_rank=shape.ep_rank, tokens=T, routed_rows=R, active_experts=active, flops=flops,
+                         ep_rank=shape.ep_rank, routing="zipf" if shape.router == "zipf" else "balanced", tokens=T,
+                         routed_rows=R, active_experts=active, flops=flops,
                          weight_bytes=min_bytes, us_per_layer=round(us, 2), launch_mode=mode))
         print(rows[-1], flush=True)
     del layer
@@ -128,7 +133,9 @@ def main():
     ap.add_argument("--out", required=True)
     ap.add_argument("--tokens", type=int, nargs="*", default=list(DEFAULT_TOKENS))
     ap.add_argument("--models", nargs="*", default=["mixtral", "qwen", "qwen2_57b"])
-    ap.add_argument("--shard", default=None, help="MODEL:TP:EP, measure this one shard in this process")
+    ap.add_argument("--no-skew", action="store_true", help="balanced routing only")
+    ap.add_argument("--shard", default=None,
+                    help="MODEL:TP:EP[:EP_RANK[:zipf]], measure this one shard in this process")
     args = ap.parse_args()
     bases = {"mixtral": I.MIXTRAL, "qwen": I.QWEN, "qwen2_57b": I.QWEN2_57B}
 
@@ -139,8 +146,14 @@ def main():
             w.writerows(rows)
 
     if args.shard is not None:
-        m, tp, ep = args.shard.split(":")
-        write(measure(bases[m].shard(tp_degree=int(tp), tp_rank=0, ep_degree=int(ep), ep_rank=0), args.tokens))
+        from dataclasses import replace
+        parts = args.shard.split(":")
+        m, tp, ep = parts[0], int(parts[1]), int(parts[2])
+        rank = int(parts[3]) if len(parts) > 3 else 0
+        shape = bases[m].shard(tp_degree=tp, tp_rank=0, ep_degree=ep, ep_rank=rank)
+        if len(parts) > 4 and parts[4] == "zipf":
+            shape = replace(shape, router="zipf")
+        write(measure(shape, args.tokens))
         return
     # One child process per shard (this one never touches the GPU).  In the memory-bound regime a
     # layer whose weights were allocated after a larger layer was freed, from torch's cache or anew,
@@ -151,12 +164,17 @@ def main():
     rows = []
     for m in args.models:
         for tp, ep in legal_shards(bases[m]):
-            with tempfile.TemporaryDirectory() as d:
-                part = os.path.join(d, "part.csv")
-                subprocess.run([sys.executable, "-m", "paper_2508_19373_amd.latency_table", "--out", part, "--shard",
-                                "%s:%d:%d" % (m, tp, ep), "--tokens", *[str(t) for t in args.tokens]], check=True)
-                with open(part, newline="") as f:
-                    rows += list(csv.DictReader(f))
+            jobs = [("%s:%d:%d" % (m, tp, ep), args.tokens)]
+            if ep > 1 and not args.no_skew:
+                skewed = [t for t in SKEWED_TOKENS if t <= max(args.tokens)]
+                jobs += [("%s:%d:%d:%d:zipf" % (m, tp, ep, rank), skewed) for rank in (0, ep - 1)]
+            for spec, tokens in jobs:
+                with tempfile.TemporaryDirectory() as d:
+                    part = os.path.join(d, "part.csv")
+                    subprocess.run([sys.executable, "-m", "paper_2508_19373_amd.latency_table", "--out", part,
+                                    "--shard", spec, "--tokens", *[str(t) for t in tokens]], check=True)
+                    with open(part, newline="") as f:
+                        rows += list(csv.DictReader(f))
     write(rows)
     print("wrote %d rows to %s" % (len(rows), args.out))
 

@@ -131,6 +131,8 @@ class ExpertLatencyTable:
         self.curves: Dict[Tuple[str, int, int], List[Tuple[float, float]]] = {}
         with open(path) as f:
             for r in csv.DictReader(f):
+                if r.get("routing", "balanced") != "balanced":
+                    continue  # the search's T_e is the balanced-routing curve of each shard
                 key = (r["model"], int(r["tp"]), int(r["ep"]))
                 self.curves.setdefault(key, []).append((math.log(float(r["tokens"])), math.log(float(r["us_per_layer"]))))
         for c in self.curves.values():

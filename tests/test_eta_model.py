@@ -74,3 +74,32 @@ def test_measured_table_holdout_error_below_ten_percent():
     # growing with tokens at prefill sizes
     mix = {r["tokens"]: r["us_per_layer"] for r in rows if r["model"] == I.MIXTRAL.name and r["tp"] == 1 and r["ep"] == 1}
     assert mix[64] < 1.1 * mix[16] and mix[8192] > 1.6 * mix[4096]
+
+
+def test_unmeasured_shard_is_predicted_from_the_measured_ones():
+    # what the simulator is for: the latency of a configuration that was not measured.  Leave one
+    # (model, E_t, E_e) shard out at a time, all its token counts and routings, fit on the rest.
+    rows = M.load_table(TABLE)
+    by_shard = M.group_holdout_error(rows, lambda r: (r["model"], r["tp"], r["ep"]), n_estimators=40)
+    assert len(by_shard) == 29
+    means = np.array([v[0] for v in by_shard.values()])
+    print("leave-one-shard-out: mean of shard means %.3f, worst shard mean %.3f, largest single error %.3f"
+          % (means.mean(), means.max(), max(v[1] for v in by_shard.values())))
+    assert means.mean() < 0.12          # measured 0.096; the paper reports < 10 % for its compute model
+    assert np.median(means) < 0.10
+    # the miss is stated, not hidden: the shards at the edge of the grid (Qwen1.5 with its intermediate
+    # size cut in 8, a slice of 176 zero-padded to 192) are off by 30 % on average
+    assert means.max() < 0.45
+
+
+def test_skewed_rows_use_the_rows_the_shard_receives():
+    rows = M.load_table(TABLE)
+    skew = [r for r in rows if r["routing"] == "zipf"]
+    assert len(skew) >= 150 and {r["ep_rank"] for r in skew} >= {0.0, 1.0, 3.0}
+    hot = [r for r in skew if r["model"] == I.MIXTRAL.name and r["tp"] == 1 and r["ep"] == 4 and r["ep_rank"] == 0 and r["tokens"] == 8192][0]
+    cold = [r for r in skew if r["model"] == I.MIXTRAL.name and r["tp"] == 1 and r["ep"] == 4 and r["ep_rank"] == 3 and r["tokens"] == 8192][0]
+    assert hot["routed_rows"] > 0.5 * 2 * 8192 and cold["routed_rows"] < 0.15 * 2 * 8192
+    assert M.expected_rows(hot) == hot["routed_rows"] and M.module_flops(hot) > 5 * M.module_flops(cold)
+    assert hot["us_per_layer"] > 3 * cold["us_per_layer"]          # the load imbalance the paper describes
+    bal = dict(hot, routing="balanced")
+    assert M.expected_rows(bal) == 8192 * 2 / 4
