@@ -31,8 +31,9 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 # (FETCH_SIZE, WRITE_SIZE in KiB per dispatch; see profiles/<workload>_rocprofv3.txt), each scaled by
 # what the same counter reads for a plain 1 GiB device copy: FETCH_SIZE x 2.0, WRITE_SIZE x 1.0.
 MEASURED_TRAFFIC_BYTES = {
-    "mixtral_prefill": (1958869.5 * 2.0 + 232964.5) * 1024,
-    "mixtral_decode": (936905.7 * 2.0 + 898.8) * 1024,
+    "mixtral_prefill": (1958763.1 * 2.0 + 232963.1) * 1024,
+    "mixtral_decode": (936763.1 * 2.0 + 898.7) * 1024,
+    "qwen_prefill": (405805.6 * 2.0 + 45056.0) * 1024,
 }
 
 # measured after the main workload in the same run (`also` in the JSON line)
@@ -300,7 +301,8 @@ def main():
             also[w] = {"workload": a["desc"], "us_per_layer": a["ms_per_step"] * 1e3, "launch_mode": a["mode"],
                        "tflops": a["tflops"], "pct_mfma_peak": 100.0 * a["tflops"] / PEAK_BF16_TFLOPS,
                        "min_bytes_gbs": a["gbs"], "pct_hbm_peak": 100.0 * a["gbs"] / PEAK_HBM_GBS,
-                       "bound": r["bound"], "frac": r["frac"], "kernel": r["kernel"], "kernel_ms": r["ms"],
+                       "bound": r["bound"], "frac": r["frac"], "traffic": r["traffic"], "kernel": r["kernel"],
+                       "kernel_ms": r["ms"],
                        "breakdown_ms": a["br"]}
             del a
             torch.cuda.empty_cache()
