@@ -122,6 +122,8 @@ bool launch_walk(const gw::WalkPlan& plan, const uint16_t* A, const int32_t* exp
   if constexpr (MT == 1) {
     MOE_WALK(16, 14)
     MOE_WALK(16, 11)
+  }
+  if constexpr (MT == 1 || !GATEUP) {  // with 32 rows per pass only the down projection fits sixteen wavefronts
     MOE_WALK(16, 8)
     MOE_WALK(16, 7)
     MOE_WALK(16, 5)
@@ -167,7 +169,7 @@ hipError_t launch_pair_decode(const void* x_perm, RowMap rows, const int32_t* ex
     if (err != hipSuccess) return err;
   }
   if (flags & MOE_FFN_SKIP_DOWN) return hipSuccess;
-  const gw::WalkPlan p2 = gw::plan_for(I_s, MT);
+  const gw::WalkPlan p2 = gw::plan_for(I_s, MT, true);
   if (!y_bf16 && p2.nw != 0 && H % 16 == 0 && (p2.slices == 1 || workspace != nullptr)) {
     void* out = p2.slices == 1 ? y_perm : workspace;
     if (launch_walk<MT, false>(p2, hw, expert_offsets, n_local, static_cast<const uint16_t*>(w_down),
@@ -239,8 +241,10 @@ inline bool prefer_walk(int cap_rows, int est_rows, int n_local, int n_out, int 
   const int mt = decode_mt(cap_rows, est_rows, n_local);
   const double passes = ceil(rows_hi / (16.0 * mt));
   const double bytes = mats * n_local * (double)n_out * K * 2.0;
-  const double rate = gw::plan_for(K, mt).nw == 0 ? 3.0e12
-                                                  : (mt == 1 ? (gateup ? 6.0e12 : 5.4e12) : (gateup ? 5.3e12 : 4.9e12));
+  const gw::WalkPlan wp = gw::plan_for(K, mt, !gateup);
+  const double rate = wp.nw == 0 ? 3.0e12
+                                                  : (mt == 1 ? (gateup ? 6.0e12 : 5.4e12)
+                                                             : (gateup ? 5.3e12 : (wp.nw == 16 ? 5.9e12 : 4.9e12)));
   const double walk = passes * (bytes / rate + 5e-6);
   const int ncb = (n_out + (gateup ? 127 : 255)) / (gateup ? 128 : 256);
   const int slices = gateup ? 1 : gg::k_slices_for(est_rows, n_local, ncb, K, exact);
@@ -293,7 +297,7 @@ size_t ffn_workspace_bytes(int cap_rows, int est_rows, int n_local, int H, int I
   // what the tiled kernels need is always covered: MOE_FFN_TILED may overrule the estimate
   const size_t tiled = (size_t)gg::slice_plan(cap_rows, (H + 255) / 256, I_s).scratch_rows * H * sizeof(float);
   if (!prefer_walk(cap_rows, est_rows, n_local, H, I_s, false)) return tiled;
-  const gw::WalkPlan p2 = gw::plan_for(I_s, decode_mt(cap_rows, est_rows, n_local));
+  const gw::WalkPlan p2 = gw::plan_for(I_s, decode_mt(cap_rows, est_rows, n_local), true);
   const int slices = p2.nw == 0 ? 1 : p2.slices;
   const size_t walk = slices > 1 ? (size_t)slices * cap_rows * H * sizeof(float) : 0;
   return walk > tiled ? walk : tiled;
@@ -307,7 +311,7 @@ void ffn_plan(int cap_rows, int est_rows, int n_local, int H, int I_s, int32_t o
   out[1] = walk2;
   out[2] = mt;
   if (walk2) {
-    const gw::WalkPlan p2 = gw::plan_for(I_s, mt);
+    const gw::WalkPlan p2 = gw::plan_for(I_s, mt, true);
     out[3] = p2.nw == 0 ? 1 : p2.slices;
   } else {
     out[3] = gg::slice_plan(cap_rows, (H + 255) / 256, I_s).max_slices;
