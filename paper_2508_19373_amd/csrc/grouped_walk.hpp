@@ -255,9 +255,9 @@ inline WalkPlan plan_for(int K, int mt, bool down = false) {
     }
     if (mt == 2 && down) {
       // the down projection's registers (no second weight matrix) leave room for sixteen wavefronts of up
-      // to 8 steps at 128 VGPRs also with 32 rows per pass: 5.95 TB/s against 4.9 with eight wavefronts
-      // (Mixtral TP=4 shard, K = 3584, 48-64 tokens: 39.1-39.9 us, tiled 43.0).  The gate/up projection
-      // spills in that shape (97 us against 91 with eight wavefronts).
+      // to 8 steps at 128 VGPRs also with 32 rows per pass (Mixtral TP=4 shard, K = 3584, 48-64 tokens:
+      // 39.1-39.9 us replayed alone, tiled 43.0; layer 162.8 -> 160.6 us).  The gate/up projection spills
+      // in that shape (97 us against 91 with eight wavefronts).
       const int cand16[4] = {8, 7, 5, 4};
       for (int st : cand16)
         if (steps32 == 16 * st) return WalkPlan{16, st, 1};
