@@ -296,7 +296,11 @@ def main():
             if w == args.workload:
                 continue
             # (their own step counts: short runs of these small layers are dominated by the clock settling)
-            a = measure(w, 50, 30, args, torch, np, B, I, ExpertShardLayer, bf16_tensor)
+            try:
+                a = measure(w, 50, 30, args, torch, np, B, I, ExpertShardLayer, bf16_tensor)
+            except Exception as e:  # the headline line is printed whatever happens to an extra workload
+                also[w] = {"error": "%s: %s" % (type(e).__name__, e)}
+                continue
             r = a["roofline"]
             also[w] = {"workload": a["desc"], "us_per_layer": a["ms_per_step"] * 1e3, "launch_mode": a["mode"],
                        "tflops": a["tflops"], "pct_mfma_peak": 100.0 * a["tflops"] / PEAK_BF16_TFLOPS,
