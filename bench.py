@@ -6,9 +6,9 @@ A step is one pass of the whole hot path (route -> permute -> grouped SwiGLU FFN
 resident in HBM.  Prints ONE JSON line: whole-layer throughput in bf16 TFLOP/s (algorithmic
 FLOPs only), ms per step, a roofline object for the dominant kernel measured live with
 events on the launch stream, and the CPU oracle timed on a bounded sample of the same
-workload.  The line's `also` object holds the same measurement (50 steps after 30) of two more
-shapes taken in the same process: a decode shape (Mixtral-sized, 16 tokens: HBM-bound) and the
-Qwen-sized prefill, the shape furthest from its roofline.
+workload.  The line's `also` object holds the same measurement (50 steps after 30) of the other
+target shapes, taken in the same process: the Mixtral-sized decode batch, its tensor-parallel and
+expert-parallel shards, and the Qwen-sized layer at prefill and decode sizes.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload mixtral_prefill] [--no-also]
 """
@@ -36,8 +36,9 @@ MEASURED_TRAFFIC_BYTES = {
     "qwen_prefill": (405805.6 * 2.0 + 45056.0) * 1024,
 }
 
-# measured after the main workload in the same run (`also` in the JSON line)
-ALSO_WORKLOADS = ("mixtral_decode", "qwen_prefill")
+# measured after the main workload in the same run (`also` in the JSON line): the other target shapes
+ALSO_WORKLOADS = ("mixtral_decode", "mixtral_tp4_prefill", "mixtral_tp4_decode", "mixtral_ep4_hot", "mixtral_ep4_cold",
+                  "qwen_prefill", "qwen_decode")
 
 # name -> (inputs.WORKLOADS key, token count, description)
 WORKLOADS = {
@@ -215,7 +216,7 @@ def main():
                     help="replay the layer as one HIP graph (auto: when an eager step takes < 1 ms)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens the oracle is timed on (0 = auto)")
     ap.add_argument("--no-also", action="store_true",
-                    help="skip the two extra workloads (a decode shape and the Qwen-sized prefill) measured after the main one")
+                    help="skip the other target shapes measured after the main workload")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU's shard: this build has no multi-GPU path; run with --gpus 1")
@@ -286,8 +287,8 @@ def main():
         "launch_mode": mode, "eager_ms_per_step": eager_ms, "step_ms_median": step_median_ms,
         "step_ms_min": step_min_ms, "device_copy_gbs": copy_gbs, "breakdown_ms": br, "input_gen_s": gen_s, "roofline": roofline, "cpu_baseline": cpu,
     }
-    # ---- two more shapes in the same process, so that one run covers a decode shape (HBM-bound) and
-    # the prefill shape furthest from its roofline beside the headline
+    # ---- the other target shapes in the same process, so that one run of the default command covers
+    # every shape the targets are stated for
     if not args.no_also:
         del m, layer, x, logits, li
         torch.cuda.empty_cache()
